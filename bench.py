@@ -1,0 +1,142 @@
+"""Benchmark of the C2T tree-construction hot path on one MI355X.
+
+A step is one whole draft phase over one batch of synthetic logits: reset, max_depth x
+expand_layer (logits pass + score/prune), finalize_tree, with every input resident in HBM.
+Prints ONE JSON line: whole-job throughput in draft-tree nodes scored per second, the HBM
+roofline of the logits-pass kernel (timed with HIP events on its own stream inside the timed
+region) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (default: batched serving, B=64, V=128256)")
+    ap.add_argument("--splits", default="", help="row splits 'first,other' (0 = default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how "
+              "the path would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_13652_amd import C2TContext, stream_read
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[a.workload]
+    B, V, F, K, D, N, h = (cfg[k] for k in ("B", "V", "F", "K", "D", "N", "h"))
+    esz = 4 if cfg["dtype"] == "f32" else 2
+    cls = W.classifier(cfg, W.classifier_seed(a.workload))
+    layers = [W.logits_layer(cfg, l, device=dev) for l in range(D)]
+    ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"], device=dev)
+    ctx.set_classifier(*cls)
+    if a.splits:
+        ctx.set_row_splits(*[int(x) for x in a.splits.split(",")])
+    out = ctx.new_tree_out()
+
+    def step():
+        ctx.reset()
+        for l in range(D):
+            ctx.expand_layer(layers[l])
+        ctx.finalize_tree(out)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(a.steps * D)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k1_ms = ctx.profile_read(a.steps * D)
+    ctx.profile_enable(0)
+    rows = ctx.layer_rows().cpu().numpy()[:D].astype(np.int64)      # rows consumed by each layer's expand
+    scored_per_step = int(rows.sum()) * K
+    k1_ms = np.array(k1_ms, np.float64).reshape(a.steps, D)
+    bytes_layer = rows * V * esz
+    k1_total_s = k1_ms.sum() / 1e3
+    achieved = bytes_layer.sum() * a.steps / k1_total_s / 1e9       # GB/s over every logits-pass launch
+    full = rows == B * F
+    per_layer = [dict(layer=int(l), rows=int(rows[l]), mbytes=round(bytes_layer[l] / 1e6, 2),
+                      us=round(float(k1_ms[:, l].mean() * 1e3), 2),
+                      gbps=round(float(bytes_layer[l] / (k1_ms[:, l].mean() / 1e3) / 1e9), 1)) for l in range(D)]
+
+    # practical ceiling: plain streaming read of a buffer larger than the last-level cache
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    acc = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(2):
+        stream_read(big, acc)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        stream_read(big, acc)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbps = 5 * big.numel() / (e0.elapsed_time(e1) / 1e3) / 1e9
+    del big
+
+    n_nodes = out["n_nodes"].cpu().numpy()
+    rec = {
+        "metric": "draft-tree nodes scored/sec + logits-pass HBM GB/s (fraction of peak), 1 GPU",
+        "value": scored_per_step * a.steps / dt,
+        "unit": "nodes scored/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt / a.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "classifier_seed": W.classifier_seed(a.workload),
+                   "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "k_logits_pass", "launches": int(a.steps * D),
+                     "avg_launch_us": float(k1_ms.mean() * 1e3),
+                     "algorithmic_bytes_per_launch": float(bytes_layer.mean()),
+                     "full_layer_gbps": float(np.mean([p["gbps"] for p, f in zip(per_layer, full) if f])) if full.any() else None,
+                     "stream_read_gbps": stream_gbps, "per_layer": per_layer},
+    }
+
+    if not a.no_cpu_baseline:
+        from oracle import RefTree
+        # bounded sample: whole draft phases of the first n sequences, one thread
+        per_seq_elems = (1 + (D - 1) * F) * V
+        nseq = a.cpu_seqs or max(1, min(B, int(1.0e9 / per_seq_elems)))
+        sl = [W.as_numpy_bits(x[:nseq].cpu()) for x in layers]
+        t = RefTree(nseq, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"])
+        t.set_classifier(*cls)
+        t.reset()
+        c0 = time.perf_counter()
+        for l in range(D):
+            if t.frontier()["n_frontier"].sum() == 0:
+                break
+            t.expand_layer(sl[l], threads=1)
+        t.finalize()
+        cdt = time.perf_counter() - c0
+        scored = int(t.audit()["scored"].sum())
+        rec["cpu_baseline"] = {"value": scored / cdt, "unit": "nodes scored/s", "cores": 1, "kind": "oracle",
+                               "sample": "whole draft phases of the first %d of %d sequences of %s, %d candidates, %.1f s"
+                                         % (nseq, B, a.workload, scored, cdt)}
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

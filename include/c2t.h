@@ -1,0 +1,166 @@
+/*
+ * c2t.h — C ABI of the MI355X (gfx950) implementation of the per-layer hot path of
+ * C2T classifier-based token-tree construction (arXiv 2502.13652).
+ *
+ * One draft phase is Algorithm 1 of the paper: starting from the root token, each
+ * iteration takes the draft model's logits for every node of the current tree layer
+ * ("frontier"), keeps the TopK most probable children per node (Sec. 4.2.2, purpose 1),
+ * gives each child the features joint probability P (Eq. 1), entropy H of the
+ * distribution it was drawn from (Eq. 2, first line, natural log) and depth d,
+ * scores it with the two-layer ReLU FFN classifier C = sigmoid(F(P,H,d)) (Eq. 3,
+ * Sec. 4.1), drops children with C <= beta (first pruning, Sec. 4.2.1), keeps the
+ * `max_frontier` most confident survivors (second pruning, Sec. 4.2.2, purpose 2)
+ * within a total node budget (EAGLE-2's N, Sec. 2.2), and appends them to the tree.
+ * The draft-model call between layers is the caller's: it reads the new frontier
+ * with c2t_get_frontier, runs its model, and hands the logits to c2t_expand_layer.
+ * c2t_finalize_tree emits what tree attention (Sec. 2.2) needs for verification.
+ *
+ * Conventions
+ *  - Every pointer is tagged [host] or [device] below.  The library never allocates,
+ *    frees or synchronises device memory: the caller owns all of it, including the
+ *    workspace, and passes the stream (a hipStream_t as void*, NULL = default stream)
+ *    that every kernel of a call is enqueued on.  Calls return after enqueueing.
+ *  - Return value: 0 = C2T_OK, negative = error (c2t_strerror).  Argument and state
+ *    errors are found on the host before anything is enqueued.  Data errors (NaN or
+ *    +inf logits, a row with no finite logit) never fail a call: the row yields no
+ *    candidates and bit 0 of that sequence's status word is set.
+ *  - Call order per draft phase: c2t_reset, then at most max_depth x c2t_expand_layer,
+ *    then c2t_finalize_tree; anything else is C2T_ERR_STATE.
+ *  - Ties: a row's TopK is ordered by (logit desc, token id asc); survivors of a layer
+ *    are ranked by (classifier logit z desc, token id asc, parent slot asc).
+ *  - Decisions are taken on the classifier's pre-sigmoid logit z in fp32:
+ *    C > beta  <=>  z > logit(beta), logit(beta) rounded once to fp32 (beta = 0 keeps all).
+ */
+#ifndef C2T_H
+#define C2T_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct c2t_ctx c2t_ctx; /* opaque, host memory */
+
+enum { C2T_F32 = 0, C2T_BF16 = 1 };
+
+enum {
+  C2T_OK = 0,
+  C2T_ERR_INVALID_ARG = -1, /* NULL pointer, value out of range                        */
+  C2T_ERR_UNSUPPORTED = -2, /* misaligned logits / stride, size above a compiled limit */
+  C2T_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned (256 B) or too small         */
+  C2T_ERR_STATE = -4,       /* call out of order, classifier not set                   */
+  C2T_ERR_HIP = -5          /* a HIP runtime call failed (launch, memcpy)               */
+};
+
+/* Limits compiled into the kernels. */
+#define C2T_MAX_TOP_K 64
+#define C2T_MAX_FRONTIER 64
+#define C2T_MAX_HIDDEN 256
+#define C2T_MAX_BUDGET 1024
+#define C2T_MAX_CANDIDATES 2048 /* max_frontier * top_k */
+
+typedef struct {
+  int32_t batch;        /* B: independent sequences                                   */
+  int32_t vocab;        /* V: logits per row, >= top_k                                */
+  int32_t max_frontier; /* F: nodes expanded per layer (second pruning width)         */
+  int32_t top_k;        /* K: children scored per frontier node                       */
+  int32_t max_depth;    /* D = d_max of Algorithm 1                                   */
+  int32_t budget;       /* N: max candidate nodes per sequence, root excluded         */
+  int32_t hidden;       /* h: classifier hidden width                                 */
+  int32_t logits_dtype; /* C2T_F32 or C2T_BF16                                        */
+  float beta;           /* 0 <= beta < 1                                              */
+  int32_t entropy_top_m; /* 0: entropy over the full vocabulary (Eq. 2, line 1);
+                            M > 0: over the M most probable tokens (Eq. 2, line 2)    */
+} c2t_config;
+
+/* Caller-owned [device] output buffers of c2t_finalize_tree, N = budget.
+ * Node order is breadth first, within a layer by rank.  Entries >= n_nodes[b] are
+ * written as tokens/parent -1, position 0, reals 0, mask 0. */
+typedef struct {
+  int32_t* tokens;     /* [B][N] token id of each candidate node                       */
+  int32_t* parent;     /* [B][N] node index of the parent, -1 = child of the root      */
+  int32_t* position;   /* [B][N] depth + 1 (offset from the root token)                */
+  float* conf;         /* [B][N] C = sigmoid(z)                                        */
+  float* joint_prob;   /* [B][N] P, Eq. 1                                              */
+  float* entropy;      /* [B][N] H of the row the node was drawn from, Eq. 2           */
+  int32_t* n_nodes;    /* [B]                                                          */
+  uint8_t* mask;       /* [B][N][N] mask[i][j] = 1 iff j == i or j is an ancestor of i;
+                          the root is not a slot (every node attends to it)            */
+  uint32_t* status;    /* [B] bit 0: a consumed row held NaN / +inf / no finite logit  */
+} c2t_tree_out;
+
+/* Bytes of device workspace a context of this configuration needs.  [host] out. */
+int c2t_workspace_bytes(const c2t_config* cfg, size_t* out);
+
+/* Create a context over a caller-owned [device] workspace (256-byte aligned, at least
+ * c2t_workspace_bytes).  The workspace must stay valid until c2t_destroy.  [host] out. */
+int c2t_create(const c2t_config* cfg, void* dev_workspace, size_t workspace_bytes, c2t_ctx** out);
+void c2t_destroy(c2t_ctx* ctx);
+
+/* Classifier parameters of Eq. 3, [host] pointers, copied to the workspace on `stream`
+ * (the host arrays may be reused once the call returns).  W1 is [h][3] with input order
+ * (P, H, d); b1 [h]; w2 [h]; b2 scalar.  z = b2 + sum_j w2[j] * relu(W1[j].(P,H,d) + b1[j]),
+ * evaluated in fp32 as a fixed chain of fused multiply-adds, j ascending. */
+int c2t_set_classifier(c2t_ctx* ctx, const float* W1, const float* b1, const float* w2, float b2,
+                       void* stream);
+
+/* Start a draft phase (Algorithm 1, first four lines): tree = {root}, frontier = {root},
+ * P_root = 1, depth 0, every sequence's node count and status cleared. */
+int c2t_reset(c2t_ctx* ctx, void* stream);
+
+/* One iteration of Algorithm 1's loop for every sequence.
+ * logits [device]: [B][F][row_stride_elems] of the configured dtype; row f of sequence b is
+ * the draft model's output for frontier slot f.  Only rows f < n_frontier[b] are read
+ * (one row per sequence in the first layer).  The base address must be 16-byte aligned and
+ * row_stride_elems >= vocab a multiple of 16 bytes, else C2T_ERR_UNSUPPORTED.
+ * Effects: appends the kept children to the tree, replaces the frontier by them. */
+int c2t_expand_layer(c2t_ctx* ctx, const void* logits, int64_t row_stride_elems, void* stream);
+
+/* [device] pointers into the workspace describing the current frontier, valid until the
+ * next reset/expand: tokens [B][F] (token id of each frontier node; -1 for the root slot),
+ * parent_slot [B][F] (slot, in the previous frontier, of the node's parent: which of the
+ * previous rows it was drawn from), n_frontier [B] (0 = this sequence's loop has ended:
+ * Algorithm 1's guard "exists C_i > beta").  Any of the three out-pointers may be NULL. */
+int c2t_get_frontier(c2t_ctx* ctx, const int32_t** tokens, const int32_t** parent_slot,
+                     const int32_t** n_frontier);
+
+/* Every candidate given a confidence in the last expanded layer, [device] pointers into the
+ * workspace, arrays [B][F*K] indexed slot*K + rank_in_row (entries of unused slots are stale):
+ * token, p (generation probability), P, H, z, kept (1 = appended to the tree); n_cand [B].
+ * Any out-pointer may be NULL. */
+int c2t_get_candidates(c2t_ctx* ctx, const int32_t** n_cand, const int32_t** token, const float** p,
+                       const float** P, const float** H, const float** z, const int32_t** kept);
+
+/* Emit the verification inputs of the tree built so far into caller-owned [device] buffers
+ * (every field of `out` non-NULL). */
+int c2t_finalize_tree(c2t_ctx* ctx, const c2t_tree_out* out, void* stream);
+
+/* Per-launch accounting for benchmarks: [device] pointer to int32 [max_depth + 1];
+ * entry l = number of logits rows layer l's expand consumed (sum over sequences of
+ * n_frontier), filled as the layers run. */
+int c2t_get_layer_rows(c2t_ctx* ctx, const int32_t** layer_rows);
+
+/* Launch-shape override for experiments: number of workgroups a logits row is split over
+ * in the first layer (one row per sequence) and in later layers; 0 = library default. */
+int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
+
+/* Optional timing of the logits-pass kernel with HIP events recorded on the caller's
+ * stream around each launch.  c2t_profile_enable creates `capacity` event pairs (host
+ * resources; 0 disables and destroys them).  After the caller has synchronised the stream,
+ * c2t_profile_read writes the duration in milliseconds of each launch recorded since the
+ * last read to ms[0..*n) ([host], capacity given in *n on entry) and forgets them. */
+int c2t_profile_enable(c2t_ctx* ctx, int32_t capacity);
+int c2t_profile_read(c2t_ctx* ctx, float* ms, int32_t* n);
+
+/* Plain streaming read of `bytes` (multiple of 16) of [device] memory, summed into one
+ * uint32 at [device] out: the practical HBM read ceiling to compare the logits pass with. */
+int c2t_stream_read(const void* dev_ptr, size_t bytes, uint32_t* dev_out, void* stream);
+
+const char* c2t_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* C2T_H */

@@ -1,0 +1,332 @@
+// Host side of the C ABI declared in include/c2t.h: argument checks, workspace carving,
+// launch shapes.  Every step of the path runs in the kernels of k_logits.h / k_tree.h;
+// nothing here touches logits or tree data on the host, allocates device memory or
+// synchronises the device.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/c2t.h"
+#include "k_logits.h"
+#include "k_tree.h"
+
+using namespace c2t;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+constexpr int MAX_LDS_MAP_BYTES = 48 * 1024;   // cell map of one workgroup
+constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
+constexpr int TARGET_WORKGROUPS = 2048;        // enough to fill 256 CUs several times over
+
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+  size_t cls, n_nodes, n_frontier, status, n_cand, layer_rows;
+  size_t fr_tok, fr_pslot, fr_node, fr_P;
+  size_t t_tok, t_parent, t_depth, t_P, t_H, t_z;
+  size_t c_tok, c_p, c_P, c_H, c_z, c_kept;
+  size_t part, part_topv, part_topi;
+  size_t total;
+  int64_t partial_slots;
+};
+
+int epc_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? 8 : 4; }
+int keybytes_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? 2 : 4; }
+int chunks_of(const c2t_config& c) { return (c.vocab + epc_of(c) - 1) / epc_of(c); }
+// fewest splits for which one workgroup's cell map fits its LDS budget
+int min_splits(const c2t_config& c) {
+  const int max_cells = MAX_LDS_MAP_BYTES / keybytes_of(c);
+  return (chunks_of(c) + max_cells - 1) / max_cells;
+}
+
+int check_config(const c2t_config* c) {
+  if (!c) return C2T_ERR_INVALID_ARG;
+  if (c->batch <= 0 || c->vocab <= 0 || c->max_frontier <= 0 || c->top_k <= 0 || c->max_depth <= 0 ||
+      c->budget <= 0 || c->hidden <= 0)
+    return C2T_ERR_INVALID_ARG;
+  if (!(c->beta >= 0.0f && c->beta < 1.0f)) return C2T_ERR_INVALID_ARG;
+  if (c->logits_dtype != C2T_F32 && c->logits_dtype != C2T_BF16) return C2T_ERR_INVALID_ARG;
+  if (c->top_k > c->vocab || c->entropy_top_m < 0) return C2T_ERR_INVALID_ARG;
+  if (c->top_k > C2T_MAX_TOP_K || c->max_frontier > C2T_MAX_FRONTIER || c->hidden > C2T_MAX_HIDDEN ||
+      c->budget > C2T_MAX_BUDGET || (int64_t)c->max_frontier * c->top_k > C2T_MAX_CANDIDATES)
+    return C2T_ERR_UNSUPPORTED;
+  if (c->entropy_top_m != 0) return C2T_ERR_UNSUPPORTED;
+  if ((int64_t)c->batch * c->max_frontier * min_splits(*c) > (1 << 24)) return C2T_ERR_UNSUPPORTED;
+  return C2T_OK;
+}
+
+Layout make_layout(const c2t_config& c) {
+  Layout L;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  const size_t B = c.batch, F = c.max_frontier, K = c.top_k, N = c.budget, h = c.hidden;
+  L.cls = take((5 * h + 1) * 4);
+  L.n_nodes = take(B * 4); L.n_frontier = take(B * 4); L.status = take(B * 4); L.n_cand = take(B * 4);
+  L.layer_rows = take((c.max_depth + 1) * 4);
+  L.fr_tok = take(B * F * 4); L.fr_pslot = take(B * F * 4); L.fr_node = take(B * F * 4); L.fr_P = take(B * F * 4);
+  L.t_tok = take(B * N * 4); L.t_parent = take(B * N * 4); L.t_depth = take(B * N * 4);
+  L.t_P = take(B * N * 4); L.t_H = take(B * N * 4); L.t_z = take(B * N * 4);
+  L.c_tok = take(B * F * K * 4); L.c_p = take(B * F * K * 4); L.c_P = take(B * F * K * 4);
+  L.c_H = take(B * F * K * 4); L.c_z = take(B * F * K * 4); L.c_kept = take(B * F * K * 4);
+  L.partial_slots = std::max<int64_t>((int64_t)B * F * min_splits(c), PARTIAL_SLOTS_MIN);
+  L.part = take((size_t)L.partial_slots * sizeof(RowPartial));
+  L.part_topv = take((size_t)L.partial_slots * K * 4);
+  L.part_topi = take((size_t)L.partial_slots * K * 4);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+struct c2t_ctx {
+  c2t_config cfg;
+  Layout lay;
+  char* ws;
+  TreeState st;
+  RowPartial* part;
+  float* part_topv;
+  int32_t* part_topi;
+  float z_beta;
+  int layer;          // layers expanded since reset; -1 before the first reset
+  bool have_cls, finalized;
+  int ns_first, ns_other;      // row splits in use
+  // optional event timing of the logits pass
+  std::vector<hipEvent_t> ev;
+  std::vector<float> cls_host;
+  int ev_used;
+};
+
+namespace {
+
+// default number of workgroups a row is split over when `rows` rows are launched
+int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
+  const int nmin = min_splits(c);
+  const int by_size = std::max(1, chunks_of(c) / LP_NT);   // at least one full sweep of the workgroup
+  const int64_t want = (TARGET_WORKGROUPS + rows - 1) / rows;
+  const int64_t cap = L.partial_slots / rows;
+  const int64_t ns = std::min<int64_t>(std::min<int64_t>(want, by_size), cap);
+  return (int)std::max<int64_t>(ns, nmin);
+}
+
+template <int DT>
+hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit,
+                         hipStream_t s) {
+  const c2t_config& c = x->cfg;
+  const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
+  const size_t lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)LP_ELEM_CAP * 8);
+  const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
+  hipLaunchKernelGGL((k_logits_pass<DT>), dim3(grid), dim3(LP_NT), lds, s, logits, stride, c.vocab, c.top_k,
+                     c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->part, x->part_topv,
+                     x->part_topi);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+int c2t_workspace_bytes(const c2t_config* cfg, size_t* out) {
+  if (!out) return C2T_ERR_INVALID_ARG;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  *out = make_layout(*cfg).total;
+  return C2T_OK;
+}
+
+int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
+  if (!out) return C2T_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  Layout L = make_layout(*cfg);
+  if (!ws || ((uintptr_t)ws % ALIGN) != 0 || bytes < L.total) return C2T_ERR_WORKSPACE;
+  c2t_ctx* x = new (std::nothrow) c2t_ctx();
+  if (!x) return C2T_ERR_INVALID_ARG;
+  x->cfg = *cfg; x->lay = L; x->ws = (char*)ws;
+  char* w = x->ws;
+  TreeState& s = x->st;
+  s.cls = (float*)(w + L.cls);
+  s.n_nodes = (int32_t*)(w + L.n_nodes); s.n_frontier = (int32_t*)(w + L.n_frontier);
+  s.status = (uint32_t*)(w + L.status); s.n_cand = (int32_t*)(w + L.n_cand);
+  s.layer_rows = (int32_t*)(w + L.layer_rows);
+  s.fr_tok = (int32_t*)(w + L.fr_tok); s.fr_pslot = (int32_t*)(w + L.fr_pslot);
+  s.fr_node = (int32_t*)(w + L.fr_node); s.fr_P = (float*)(w + L.fr_P);
+  s.t_tok = (int32_t*)(w + L.t_tok); s.t_parent = (int32_t*)(w + L.t_parent); s.t_depth = (int32_t*)(w + L.t_depth);
+  s.t_P = (float*)(w + L.t_P); s.t_H = (float*)(w + L.t_H); s.t_z = (float*)(w + L.t_z);
+  s.c_tok = (int32_t*)(w + L.c_tok); s.c_p = (float*)(w + L.c_p); s.c_P = (float*)(w + L.c_P);
+  s.c_H = (float*)(w + L.c_H); s.c_z = (float*)(w + L.c_z); s.c_kept = (int32_t*)(w + L.c_kept);
+  x->part = (RowPartial*)(w + L.part);
+  x->part_topv = (float*)(w + L.part_topv);
+  x->part_topi = (int32_t*)(w + L.part_topi);
+  x->z_beta = cfg->beta <= 0.0f ? -INFINITY : (float)std::log((double)cfg->beta / (1.0 - (double)cfg->beta));
+  x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0;
+  x->ns_first = default_split(*cfg, L, cfg->batch);
+  x->ns_other = default_split(*cfg, L, (int64_t)cfg->batch * cfg->max_frontier);
+  *out = x;
+  return C2T_OK;
+}
+
+void c2t_destroy(c2t_ctx* x) {
+  if (!x) return;
+  for (hipEvent_t e : x->ev) (void)hipEventDestroy(e);
+  delete x;
+}
+
+int c2t_set_classifier(c2t_ctx* x, const float* W1, const float* b1, const float* w2, float b2, void* stream) {
+  if (!x || !W1 || !b1 || !w2) return C2T_ERR_INVALID_ARG;
+  const int h = x->cfg.hidden;
+  std::vector<float>& buf = x->cls_host;      // lives as long as the context: the copy below is asynchronous
+  buf.resize((size_t)5 * h + 1);
+  std::memcpy(buf.data(), W1, (size_t)3 * h * 4);
+  std::memcpy(buf.data() + 3 * h, b1, (size_t)h * 4);
+  std::memcpy(buf.data() + 4 * h, w2, (size_t)h * 4);
+  buf[5 * h] = b2;
+  if (hipMemcpyAsync(x->st.cls, buf.data(), buf.size() * 4, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
+    return C2T_ERR_HIP;
+  x->have_cls = true;
+  return C2T_OK;
+}
+
+int c2t_reset(c2t_ctx* x, void* stream) {
+  if (!x) return C2T_ERR_INVALID_ARG;
+  if (!x->have_cls) return C2T_ERR_STATE;
+  const int n = std::max(x->cfg.batch, x->cfg.max_depth + 1);
+  hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, x->st, x->cfg.batch,
+                     x->cfg.max_frontier, x->cfg.max_depth);
+  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  x->layer = 0; x->finalized = false;
+  return C2T_OK;
+}
+
+int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, void* stream) {
+  if (!x || !logits) return C2T_ERR_INVALID_ARG;
+  const c2t_config& c = x->cfg;
+  if (x->layer < 0 || x->layer >= c.max_depth || x->finalized) return C2T_ERR_STATE;
+  if (row_stride_elems < c.vocab) return C2T_ERR_INVALID_ARG;
+  const int esz = c.logits_dtype == C2T_BF16 ? 2 : 4;
+  if (((uintptr_t)logits % 16) != 0 || (row_stride_elems * esz) % 16 != 0) return C2T_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const bool first = x->layer == 0;
+  const int rows_per_seq = first ? 1 : c.max_frontier;
+  const int nsplit = first ? x->ns_first : x->ns_other;
+  const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size();
+  if (timed && hipEventRecord(x->ev[x->ev_used], s) != hipSuccess) return C2T_ERR_HIP;
+  hipError_t e = c.logits_dtype == C2T_BF16 ? launch_logits<1>(x, logits, row_stride_elems, rows_per_seq, nsplit, s)
+                                            : launch_logits<0>(x, logits, row_stride_elems, rows_per_seq, nsplit, s);
+  if (e != hipSuccess) return C2T_ERR_HIP;
+  if (timed) {
+    if (hipEventRecord(x->ev[x->ev_used + 1], s) != hipSuccess) return C2T_ERR_HIP;
+    x->ev_used += 2;
+  }
+  const int FK = c.max_frontier * c.top_k;
+  const int nt = FK <= 256 ? 256 : 1024;
+  const size_t lds = (size_t)(((5 * c.hidden + 1 + 3) & ~3) + 4 * FK) * 4;
+  hipLaunchKernelGGL(k_score_prune, dim3(c.batch), dim3(nt), lds, s, x->st, x->part, x->part_topv, x->part_topi,
+                     nsplit, rows_per_seq, c.max_frontier, c.top_k, c.budget, c.hidden, x->layer, x->z_beta);
+  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  x->layer += 1;
+  return C2T_OK;
+}
+
+int c2t_get_frontier(c2t_ctx* x, const int32_t** tokens, const int32_t** parent_slot, const int32_t** n_frontier) {
+  if (!x) return C2T_ERR_INVALID_ARG;
+  if (tokens) *tokens = x->st.fr_tok;
+  if (parent_slot) *parent_slot = x->st.fr_pslot;
+  if (n_frontier) *n_frontier = x->st.n_frontier;
+  return C2T_OK;
+}
+
+int c2t_get_candidates(c2t_ctx* x, const int32_t** n_cand, const int32_t** token, const float** p, const float** P,
+                       const float** H, const float** z, const int32_t** kept) {
+  if (!x) return C2T_ERR_INVALID_ARG;
+  if (n_cand) *n_cand = x->st.n_cand;
+  if (token) *token = x->st.c_tok;
+  if (p) *p = x->st.c_p;
+  if (P) *P = x->st.c_P;
+  if (H) *H = x->st.c_H;
+  if (z) *z = x->st.c_z;
+  if (kept) *kept = x->st.c_kept;
+  return C2T_OK;
+}
+
+int c2t_finalize_tree(c2t_ctx* x, const c2t_tree_out* o, void* stream) {
+  if (!x || !o) return C2T_ERR_INVALID_ARG;
+  if (!o->tokens || !o->parent || !o->position || !o->conf || !o->joint_prob || !o->entropy || !o->n_nodes ||
+      !o->mask || !o->status)
+    return C2T_ERR_INVALID_ARG;
+  if (x->layer < 0) return C2T_ERR_STATE;
+  TreeOut t{o->tokens, o->parent, o->position, o->conf, o->joint_prob, o->entropy, o->n_nodes, o->mask, o->status};
+  hipLaunchKernelGGL(k_finalize, dim3(x->cfg.batch), dim3(256), 0, (hipStream_t)stream, x->st, t, x->cfg.budget);
+  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  x->finalized = true;
+  return C2T_OK;
+}
+
+int c2t_get_layer_rows(c2t_ctx* x, const int32_t** layer_rows) {
+  if (!x || !layer_rows) return C2T_ERR_INVALID_ARG;
+  *layer_rows = x->st.layer_rows;
+  return C2T_OK;
+}
+
+int c2t_set_row_splits(c2t_ctx* x, int32_t first_layer, int32_t other_layers) {
+  if (!x || first_layer < 0 || other_layers < 0) return C2T_ERR_INVALID_ARG;
+  const c2t_config& c = x->cfg;
+  const int nmin = min_splits(c);
+  const int nmax_size = std::max(1, chunks_of(c));
+  int nf = first_layer ? first_layer : default_split(c, x->lay, c.batch);
+  int no = other_layers ? other_layers : default_split(c, x->lay, (int64_t)c.batch * c.max_frontier);
+  if (nf < nmin || no < nmin || nf > nmax_size || no > nmax_size) return C2T_ERR_UNSUPPORTED;
+  if ((int64_t)c.batch * nf > x->lay.partial_slots || (int64_t)c.batch * c.max_frontier * no > x->lay.partial_slots)
+    return C2T_ERR_WORKSPACE;
+  x->ns_first = nf; x->ns_other = no;
+  return C2T_OK;
+}
+
+int c2t_profile_enable(c2t_ctx* x, int32_t capacity) {
+  if (!x || capacity < 0) return C2T_ERR_INVALID_ARG;
+  for (hipEvent_t e : x->ev) (void)hipEventDestroy(e);
+  x->ev.clear(); x->ev_used = 0;
+  for (int i = 0; i < 2 * capacity; ++i) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return C2T_ERR_HIP;
+    x->ev.push_back(e);
+  }
+  return C2T_OK;
+}
+
+int c2t_profile_read(c2t_ctx* x, float* ms, int32_t* n) {
+  if (!x || !ms || !n) return C2T_ERR_INVALID_ARG;
+  const int have = x->ev_used / 2;
+  const int cnt = std::min(have, (int)*n);
+  for (int i = 0; i < cnt; ++i)
+    if (hipEventElapsedTime(&ms[i], x->ev[2 * i], x->ev[2 * i + 1]) != hipSuccess) return C2T_ERR_HIP;
+  *n = cnt;
+  x->ev_used = 0;
+  return C2T_OK;
+}
+
+int c2t_stream_read(const void* p, size_t bytes, uint32_t* out, void* stream) {
+  if (!p || !out || bytes % 16 != 0 || ((uintptr_t)p % 16) != 0) return C2T_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(k_stream_read, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)p, bytes / 16, out);
+  return hipGetLastError() == hipSuccess ? C2T_OK : C2T_ERR_HIP;
+}
+
+const char* c2t_strerror(int code) {
+  switch (code) {
+    case C2T_OK: return "ok";
+    case C2T_ERR_INVALID_ARG: return "invalid argument";
+    case C2T_ERR_UNSUPPORTED: return "unsupported size, alignment or option";
+    case C2T_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case C2T_ERR_STATE: return "call out of order or classifier not set";
+    case C2T_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+"""Writes tests/golden/classifier_seeds.json.  Calls only the oracle (never the HIP path).
+
+A random 3->h->1 MLP drawn N(0, 0.5) is often degenerate as a pruning classifier (it keeps
+every candidate or none).  Rule, fixed before any GPU run: for each config take the smallest
+seed s >= 0 for which the oracle, run on the first min(B, 4) sequences of workload instance 0,
+  (a) lets between 20% and 80% of the second layer's candidates pass the threshold beta, and
+  (b) ends every one of those sequences with at least half of the node budget used.
+Usage: python tests/golden/make_classifier_seeds.py
+"""
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+import workloads as W  # noqa: E402
+from oracle import RefTree, ref_logit_of_beta  # noqa: E402
+
+
+def evaluate(cfg, seed, logits):
+    ns = logits[0].shape[0]
+    t = RefTree(ns, cfg["V"], cfg["F"], cfg["K"], cfg["D"], cfg["N"], cfg["h"], 0 if cfg["dtype"] == "f32" else 1, cfg["beta"])
+    t.set_classifier(*W.classifier(cfg, seed))
+    t.reset()
+    zb = ref_logit_of_beta(cfg["beta"])
+    frac = None
+    for l in range(cfg["D"]):
+        if t.frontier()["n_frontier"].sum() == 0:
+            break
+        t.expand_layer(logits[l], threads=ns)
+        if l == 1:
+            c = t.candidates()
+            tot = int(c["n_cand"].sum())
+            surv = sum(int((c["z"][b, :c["n_cand"][b]] > zb).sum()) for b in range(ns))
+            frac = surv / max(tot, 1)
+    out = t.finalize()
+    return frac, out["n_nodes"].tolist()
+
+
+def main():
+    result = {}
+    for name, cfg in W.CONFIGS.items():
+        ns = min(cfg["B"], 4)
+        logits = [W.as_numpy_bits(W.logits_layer(cfg, l, seqs=range(ns))) for l in range(cfg["D"])]
+        for seed in range(200):
+            frac, nn = evaluate(cfg, seed, logits)
+            ok = frac is not None and 0.2 <= frac <= 0.8 and min(nn) >= cfg["N"] / 2
+            print(name, seed, frac, nn, "OK" if ok else "", flush=True)
+            if ok:
+                result[name] = dict(seed=seed, layer1_pass_fraction=frac, n_nodes=nn)
+                break
+        else:
+            raise SystemExit("no seed found for " + name)
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "classifier_seeds.json"), "w") as f:
+        json.dump(result, f, indent=1)
+
+
+if __name__ == "__main__":
+    main()

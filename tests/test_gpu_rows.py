@@ -1,0 +1,108 @@
+"""GPU parity of the logits pass on adversarial rows, through the C ABI: every row is the root
+row of its own sequence (one layer, one frontier slot), so the candidate dump of the layer holds
+the row's top-K token ids, probabilities and entropy, compared with the oracle's row definition."""
+import numpy as np
+import pytest
+import torch
+
+from _harness import RTOL, close, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_round(x):
+    return torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16)
+
+
+def adversarial_rows(V, rng, bf16):
+    rows, names = [], []
+
+    def add(name, r):
+        names.append(name); rows.append(np.asarray(r, np.float32))
+
+    add("normal", 3 * rng.standard_normal(V))
+    add("all_equal", np.full(V, 1.5))
+    add("all_zero", np.zeros(V))
+    oh = np.zeros(V); oh[V // 3] = 30.0
+    add("one_hot", oh)
+    oh2 = -5 + 0.01 * rng.standard_normal(V); oh2[V - 1] = 20.0
+    add("spike_last", oh2)
+    add("ties_coarse", np.round(2 * rng.standard_normal(V)))            # a handful of distinct values
+    mi = 2 * rng.standard_normal(V); mi[rng.random(V) < 0.3] = -np.inf
+    add("minus_inf_30pct", mi)
+    mi2 = np.full(V, -np.inf); mi2[[0, V // 2, V - 1]] = [1.0, 2.0, 2.0]
+    add("only_three_finite", mi2)
+    add("sorted_desc", np.sort(3 * rng.standard_normal(V))[::-1].copy())
+    add("sorted_asc", np.sort(3 * rng.standard_normal(V)))
+    add("all_negative_large", -1000 + rng.standard_normal(V))
+    add("wide_range", 40 * rng.standard_normal(V))
+    blk = 0.1 * rng.standard_normal(V); blk[:: 8 * 256] += 10.0           # maxima land in one lane's chunks
+    add("strided_maxima", blk)
+    add("signed_zeros", np.where(rng.random(V) < 0.5, -0.0, 0.0))
+    lowhigh = -20 + rng.standard_normal(V); lowhigh[V // 2:] += 60       # reference must be raised mid-row
+    add("late_large", lowhigh)
+    return names, np.stack(rows)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,K,splits", [(32000, 10, 0), (128256, 16, 0), (128256, 32, 5), (5003, 8, 0), (5003, 64, 3),
+                                         (70, 64, 0), (152064, 32, 1)])
+def test_rows_against_oracle(dtype, V, K, splits):
+    from oracle import ref_row
+    from paper_2502_13652_amd import C2TContext
+    rng = np.random.default_rng(V * 31 + K)
+    names, rows = adversarial_rows(V, rng, dtype == "bf16")
+    B = rows.shape[0]
+    epc = 8 if dtype == "bf16" else 4
+    stride = (V + epc - 1) // epc * epc + epc          # padded stride; padding poisoned with +inf
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = torch.full((B, 1, stride), float("inf"), dtype=tdt)
+    x[:, 0, :V] = torch.from_numpy(rows).to(tdt)
+    xd = x.cuda()
+    h = 2
+    ctx = C2TContext(B, V, 1, K, 1, 1, h, 1 if dtype == "bf16" else 0, 0.0)
+    W1 = np.zeros((h, 3), np.float32); W1[0, 0] = 1
+    ctx.set_classifier(W1, np.zeros(h, np.float32), np.array([1, 0], np.float32), 0.0)
+    if splits:
+        ctx.set_row_splits(splits, splits)
+    print("rows V=%d K=%d %s splits=%d" % (V, K, dtype, splits), flush=True)
+    ctx.reset()
+    ctx.expand_layer(xd)
+    torch.cuda.synchronize()
+    c = to_np(ctx.candidates())
+    xin = x[:, 0, :V].contiguous()
+    bits = xin.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else xin.numpy()
+    for b, name in enumerate(names):
+        r = ref_row(bits[b], K)
+        assert not r["bad"], name
+        k = len(r["ids"])
+        np.testing.assert_array_equal(c["token"][b, :k], r["ids"], err_msg=name)
+        ok = close(c["p"][b, :k], r["p"].astype(np.float32), atol=1e-37)
+        assert ok.all(), "%s p: %s vs %s" % (name, c["p"][b, :k][~ok][:3], r["p"][~ok][:3])
+        assert close(c["H"][b, 0], np.float32(r["H"]), atol=2e-6 * RTOL / 1e-5).all(), "%s H: %g vs %g" % (name, c["H"][b, 0], r["H"])
+        assert (c["z"][b, :k] == c["P"][b, :k]).all() and (c["P"][b, :k] == c["p"][b, :k]).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_bad_rows_set_status_and_yield_nothing(dtype):
+    from paper_2502_13652_amd import C2TContext
+    V, K = 4096 + 8, 4
+    rng = np.random.default_rng(5)
+    rows = (2 * rng.standard_normal((5, V))).astype(np.float32)
+    rows[1, 777] = np.nan
+    rows[2, V - 1] = np.inf
+    rows[3, :] = -np.inf
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = torch.from_numpy(rows).to(tdt).view(5, 1, V).cuda()
+    ctx = C2TContext(5, V, 1, K, 1, 4, 2, 1 if dtype == "bf16" else 0, 0.0)
+    W1 = np.zeros((2, 3), np.float32); W1[0, 0] = 1
+    ctx.set_classifier(W1, np.zeros(2, np.float32), np.array([1, 0], np.float32), 0.0)
+    for splits in (1, 2):
+        ctx.set_row_splits(splits, splits)
+        ctx.reset()
+        ctx.expand_layer(x)
+        out = to_np(ctx.finalize_tree())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out["status"], [0, 1, 1, 1, 0])
+        np.testing.assert_array_equal(out["n_nodes"], [1, 0, 0, 0, 1])
+        assert (out["tokens"][1:4] == -1).all() and not out["mask"][1:4].any()

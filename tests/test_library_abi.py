@@ -1,0 +1,73 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host-side argument / state checks answer without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_13652_amd import load_library
+    return load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "c2t.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(c2t_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    syms = declared_symbols()
+    assert "c2t_expand_layer" in syms and "c2t_finalize_tree" in syms and len(syms) >= 14
+    for s in syms:
+        assert hasattr(lib, s), s
+
+
+def cfg(**kw):
+    from paper_2502_13652_amd import C2TConfig
+    base = dict(batch=2, vocab=1000, max_frontier=4, top_k=4, max_depth=3, budget=10, hidden=8, logits_dtype=1,
+                beta=0.5, entropy_top_m=0)
+    base.update(kw)
+    return C2TConfig(**base)
+
+
+def test_config_validation(lib):
+    need = ctypes.c_size_t()
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg()), ctypes.byref(need)) == 0 and need.value > 0
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg()), None) == -1
+    for bad in (dict(batch=0), dict(vocab=0), dict(top_k=0), dict(beta=1.0), dict(beta=-0.1), dict(logits_dtype=7),
+                dict(top_k=5, vocab=4), dict(budget=0), dict(hidden=0)):
+        assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**bad)), ctypes.byref(need)) == -1, bad
+    for big in (dict(top_k=65, max_frontier=1), dict(max_frontier=65, top_k=1), dict(hidden=257), dict(budget=1025),
+                dict(max_frontier=64, top_k=64), dict(entropy_top_m=1000)):
+        assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**big)), ctypes.byref(need)) == -2, big
+
+
+def test_workspace_and_state_errors(lib):
+    c = cfg()
+    need = ctypes.c_size_t()
+    lib.c2t_workspace_bytes(ctypes.byref(c), ctypes.byref(need))
+    ctx = ctypes.c_void_p()
+    assert lib.c2t_create(ctypes.byref(c), None, need.value, ctypes.byref(ctx)) == -3
+    assert lib.c2t_create(ctypes.byref(c), ctypes.c_void_p(0x1001), need.value, ctypes.byref(ctx)) == -3      # misaligned
+    assert lib.c2t_create(ctypes.byref(c), ctypes.c_void_p(0x10000), need.value - 1, ctypes.byref(ctx)) == -3  # too small
+    # a context over a fake (never dereferenced) workspace address: host-side checks only
+    assert lib.c2t_create(ctypes.byref(c), ctypes.c_void_p(0x10000), need.value, ctypes.byref(ctx)) == 0
+    assert lib.c2t_reset(ctx, None) == -4                       # classifier not set
+    assert lib.c2t_expand_layer(ctx, ctypes.c_void_p(0x20000), 1000, None) == -4   # before reset
+    assert lib.c2t_expand_layer(ctx, None, 1000, None) == -1
+    assert lib.c2t_finalize_tree(ctx, None, None) == -1
+    assert lib.c2t_set_row_splits(ctx, -1, 0) == -1
+    assert lib.c2t_set_row_splits(ctx, 1 << 20, 0) in (-2, -3)
+    assert lib.c2t_set_row_splits(ctx, 2, 3) == 0
+    p = ctypes.c_void_p()
+    assert lib.c2t_get_frontier(ctx, ctypes.byref(p), None, None) == 0 and p.value
+    assert lib.c2t_get_layer_rows(ctx, None) == -1
+    lib.c2t_destroy(ctx)
+    lib.c2t_destroy(None)
+    assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3)

@@ -88,7 +88,9 @@ typedef struct {
   int32_t* n_nodes;    /* [B]                                                          */
   uint8_t* mask;       /* [B][N][N] mask[i][j] = 1 iff j == i or j is an ancestor of i;
                           the root is not a slot (every node attends to it)            */
-  uint32_t* status;    /* [B] bit 0: a consumed row held NaN / +inf / no finite logit  */
+  uint32_t* status;    /* [B] bit 0: a consumed row held NaN / +inf / no finite logit;
+                          bit 1 (informational): a bf16 row held a logit outside
+                          [2^-25, 2^7) in magnitude and took the slower two-pass path  */
 } c2t_tree_out;
 
 /* Bytes of device workspace a context of this configuration needs.  [host] out. */

@@ -20,7 +20,11 @@ using namespace c2t;
 namespace {
 
 constexpr size_t ALIGN = 256;
-constexpr int MAX_LDS_MAP_BYTES = 48 * 1024;   // cell map of one workgroup
+// Cell map of one workgroup.  bf16: the histogram kernel holds 40 KB of static LDS, and two
+// workgroups of 1024 threads must fit the CU's 160 KB, so its map gets at most 40 KB.
+constexpr int MAX_MAP_BYTES_BF16 = 40 * 1024;
+constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
+constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
 constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
 constexpr int TARGET_WORKGROUPS = 2048;        // enough to fill 256 CUs several times over
 
@@ -31,7 +35,7 @@ struct Layout {
   size_t fr_tok, fr_pslot, fr_node, fr_P;
   size_t t_tok, t_parent, t_depth, t_P, t_H, t_z;
   size_t c_tok, c_p, c_P, c_H, c_z, c_kept;
-  size_t part, part_topv, part_topi;
+  size_t part, part_topv, part_topi, tab_e;
   size_t total;
   int64_t partial_slots;
 };
@@ -41,7 +45,7 @@ int keybytes_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? 2 : 4
 int chunks_of(const c2t_config& c) { return (c.vocab + epc_of(c) - 1) / epc_of(c); }
 // fewest splits for which one workgroup's cell map fits its LDS budget
 int min_splits(const c2t_config& c) {
-  const int max_cells = MAX_LDS_MAP_BYTES / keybytes_of(c);
+  const int max_cells = (c.logits_dtype == C2T_BF16 ? MAX_MAP_BYTES_BF16 : MAX_MAP_BYTES_F32) / keybytes_of(c);
   return (chunks_of(c) + max_cells - 1) / max_cells;
 }
 
@@ -78,6 +82,7 @@ Layout make_layout(const c2t_config& c) {
   L.part = take((size_t)L.partial_slots * sizeof(RowPartial));
   L.part_topv = take((size_t)L.partial_slots * K * 4);
   L.part_topi = take((size_t)L.partial_slots * K * 4);
+  L.tab_e = take((size_t)HP_BINS * 8);
   L.total = o;
   return L;
 }
@@ -92,6 +97,7 @@ struct c2t_ctx {
   RowPartial* part;
   float* part_topv;
   int32_t* part_topi;
+  double* tab_e;
   float z_beta;
   int layer;          // layers expanded since reset; -1 before the first reset
   bool have_cls, finalized;
@@ -107,23 +113,35 @@ namespace {
 // default number of workgroups a row is split over when `rows` rows are launched
 int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
   const int nmin = min_splits(c);
-  const int by_size = std::max(1, chunks_of(c) / LP_NT);   // at least one full sweep of the workgroup
+  const int by_size = std::max(1, chunks_of(c) / (c.logits_dtype == C2T_BF16 ? HP_NT : NT_F32));   // at least one full sweep of the workgroup
   const int64_t want = (TARGET_WORKGROUPS + rows - 1) / rows;
   const int64_t cap = L.partial_slots / rows;
   const int64_t ns = std::min<int64_t>(std::min<int64_t>(want, by_size), cap);
   return (int)std::max<int64_t>(ns, nmin);
 }
 
-template <int DT>
 hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit,
                          hipStream_t s) {
   const c2t_config& c = x->cfg;
   const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
-  const size_t lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)LP_ELEM_CAP * 8);
+  const size_t lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)SEL_ELEM_CAP * 8);
   const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
-  hipLaunchKernelGGL((k_logits_pass<DT>), dim3(grid), dim3(LP_NT), lds, s, logits, stride, c.vocab, c.top_k,
-                     c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->part, x->part_topv,
-                     x->part_topi);
+  if (c.logits_dtype == C2T_BF16) {
+    static bool lds_raised = false;       // static + dynamic LDS of this kernel exceeds the 64 KB default
+    if (!lds_raised) {
+      hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         MAX_MAP_BYTES_BF16);
+      if (e != hipSuccess) return e;
+      lds_raised = true;
+    }
+    hipLaunchKernelGGL(k_logits_hist, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, c.top_k,
+                       c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->tab_e, x->part,
+                       x->part_topv, x->part_topi);
+  } else {
+    hipLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, logits, stride, c.vocab,
+                       c.top_k, c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->part, x->part_topv,
+                       x->part_topi);
+  }
   return hipGetLastError();
 }
 
@@ -164,6 +182,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   x->part = (RowPartial*)(w + L.part);
   x->part_topv = (float*)(w + L.part_topv);
   x->part_topi = (int32_t*)(w + L.part_topi);
+  x->tab_e = (double*)(w + L.tab_e);
   x->z_beta = cfg->beta <= 0.0f ? -INFINITY : (float)std::log((double)cfg->beta / (1.0 - (double)cfg->beta));
   x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0;
   x->ns_first = default_split(*cfg, L, cfg->batch);
@@ -189,6 +208,11 @@ int c2t_set_classifier(c2t_ctx* x, const float* W1, const float* b1, const float
   buf[5 * h] = b2;
   if (hipMemcpyAsync(x->st.cls, buf.data(), buf.size() * 4, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
     return C2T_ERR_HIP;
+  // table of e^v for the bf16 value histogram (device-side fp64 exp), once per context
+  if (!x->have_cls && x->cfg.logits_dtype == C2T_BF16) {
+    hipLaunchKernelGGL(k_init_exp_table, dim3(HP_BINS / 256), dim3(256), 0, (hipStream_t)stream, x->tab_e);
+    if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  }
   x->have_cls = true;
   return C2T_OK;
 }
@@ -217,8 +241,7 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
   const int nsplit = first ? x->ns_first : x->ns_other;
   const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size();
   if (timed && hipEventRecord(x->ev[x->ev_used], s) != hipSuccess) return C2T_ERR_HIP;
-  hipError_t e = c.logits_dtype == C2T_BF16 ? launch_logits<1>(x, logits, row_stride_elems, rows_per_seq, nsplit, s)
-                                            : launch_logits<0>(x, logits, row_stride_elems, rows_per_seq, nsplit, s);
+  hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, s);
   if (e != hipSuccess) return C2T_ERR_HIP;
   if (timed) {
     if (hipEventRecord(x->ev[x->ev_used + 1], s) != hipSuccess) return C2T_ERR_HIP;
@@ -313,7 +336,7 @@ int c2t_profile_read(c2t_ctx* x, float* ms, int32_t* n) {
 
 int c2t_stream_read(const void* p, size_t bytes, uint32_t* out, void* stream) {
   if (!p || !out || bytes % 16 != 0 || ((uintptr_t)p % 16) != 0) return C2T_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(k_stream_read, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)p, bytes / 16, out);
+  hipLaunchKernelGGL(k_stream_read, dim3(256 * 8), dim3(1024), 0, (hipStream_t)stream, (const uint4*)p, bytes / 16, out);
   return hipGetLastError() == hipSuccess ? C2T_OK : C2T_ERR_HIP;
 }
 

@@ -7,27 +7,20 @@ namespace c2t {
 
 constexpr int WAVE = 64;
 
-// log2(e) split so that x*L_HI + x*L_LO reproduces x*log2(e) to ~2^-49 relative
-constexpr float L_HI = 1.44269502162933349609375f;       // fp32(log2 e)
-constexpr float L_LO = 1.925963033500011e-08f;           // log2 e - L_HI
-constexpr double L2E = 1.4426950408889634073599246810019;
-constexpr double LN2 = 0.69314718055994530941723212145818;
-
-// Per (row, split) result of the logits pass.  Sums are relative to the power-of-two
-// reference 2^c:  Z = sum_j 2^(x_j*log2e - c),  S2 = sum_j (x_j*log2e - c) * 2^(x_j*log2e - c).
-struct __attribute__((aligned(32))) RowPartial {
+// Per (row, split) result of the logits pass: Z = sum_j e^(x_j - a), S = sum_j (x_j - ref) e^(x_j - a),
+// both fp64, where ref is the segment's largest logit and the exponent offset a is ref (two-pass path)
+// or 0 (histogram path, whose table holds e^v itself).
+struct __attribute__((aligned(16))) RowPartial {
+  double ref;     // largest logit of the segment (exact); -inf for an empty or all -inf segment
+  double a;       // exponent offset of the sums
   double Z;
-  double S2;
-  float c;        // integer-valued; -inf when the segment held no finite logit
-  float m;        // largest logit of the segment
+  double S;
   int32_t n_top;  // entries of the segment's top list that are valid (<= K)
-  uint32_t flags; // bit 0: NaN or +inf seen
+  uint32_t flags; // bit 0: NaN or +inf seen; bit 1 (informational): a bf16 segment took the two-pass path
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-__device__ __forceinline__ float hw_exp2(float y) { return __builtin_amdgcn_exp2f(y); }
 
 // monotone map float -> uint32 (total order of the reals; -0 and +0 map to the same key)
 __device__ __forceinline__ uint32_t sortable_key(float x) {

@@ -6,25 +6,31 @@
 // (row, split) owns a contiguous range of chunks; lane t reads chunks t, t+NT, t+2NT, ...
 // of that range, so every load instruction of the workgroup covers NT*16 contiguous bytes.
 //
-// Softmax sums are kept relative to a per-lane power-of-two reference 2^c (c integer valued),
-// raised only if a later logit would overflow; references differ between lanes and are
-// reconciled exactly (ldexp) in fp64 when the lanes are combined.
+// Why the sums are exact.  Which children survive the two prunings is decided by comparing
+// classifier logits that are often only an ulp apart (siblings with tiny joint probability
+// share H and d), so the features must round to the same fp32 values as an fp64 evaluation
+// of the definition: fp32 exponentials are not enough.  Two paths deliver fp64-grade sums:
+//  * bf16 rows (the fast path): a bf16 logit has at most 65536 values, and all logits of
+//    practical rows lie in 32 binades, |x| in [2^-25, 2^7).  The streaming loop only COUNTS
+//    values: one LDS atomic per element into an 8192-bin histogram (sign, 5 exponent bits,
+//    7 mantissa bits).  Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v
+//    are formed in fp64 from a table of e^v: exact counts, <= 8192 fp64 terms, independent
+//    of the order in which the elements were read.
+//  * any other row (fp32 logits; bf16 rows holding a logit outside the window, a zero, an
+//    infinity or a NaN): two passes over the segment with fp64 exponentials per element.
 //
-// Top-K without data-dependent work in the streaming loop: the loop only records each
-// chunk's maximum ("cell key") in an LDS map.  Afterwards tau = K-th largest of the NT
-// per-lane maxima is a lower bound of the K-th largest logit; only cells whose key reaches
-// tau can hold a top-K element.  Those few cells are re-read (16 bytes each) and their
-// elements ranked exactly by (logit desc, id asc).
+// Top-K without data-dependent work in the streaming loop: the loop records each chunk's
+// maximum ("cell key") in an LDS map.  Afterwards a bound tau <= K-th largest logit is known
+// (exactly, from the histogram; or as the K-th largest per-lane maximum), only cells whose
+// key reaches tau can hold a top-K element, and those few cells are re-read (16 bytes each)
+// and their elements ranked exactly by (logit desc, id asc).
 #pragma once
 #include "k_common.h"
 
 namespace c2t {
 
-constexpr int LP_NT = 256;          // threads per workgroup
-constexpr int LP_NW = LP_NT / WAVE;
-constexpr int LP_CELL_CAP = 256;    // candidate cells kept per workgroup (>= 2*K)
-constexpr int LP_ELEM_CAP = LP_CELL_CAP * 8;
-constexpr float LP_HEADROOM = 64.0f;   // a lane's terms stay below 2^(HEADROOM+1)
+constexpr int SEL_CELL_CAP = 256;              // candidate cells kept per workgroup (>= 2*K)
+constexpr int SEL_ELEM_CAP = SEL_CELL_CAP * 8; // candidate elements (8 bytes each, overlaying the cell map)
 
 template <int DT> struct LogitTraits;
 template <> struct LogitTraits<1> {     // bf16
@@ -48,173 +54,232 @@ template <> struct LogitTraits<0> {     // fp32
   static __device__ __forceinline__ float from_key(key_t k) { return k; }
 };
 
-struct LaneAcc {
-  float Z0 = 0.f, Z1 = 0.f, S0 = 0.f, S1 = 0.f;
-  float c = -INFINITY;      // reference exponent (integer valued) or -inf before the first finite logit
-  float negc = 0.f;
-  float thr = -INFINITY;    // raise the reference when a chunk maximum exceeds this
-  float M = -INFINITY;      // running maximum of the lane
+// Range of chunks a (row, split) workgroup owns.
+struct Segment {
+  int c0, c1;        // chunks [c0, c1)
+  int ncell;         // c1 - c0
+  int tail_chunk;    // index of the row's last, partially valid chunk if it lies in [c0,c1), else -1
+  int tail_valid;    // its number of valid elements
 };
-
-__device__ __forceinline__ void raise_reference(LaneAcc& a, float cm) {
-  const float newc = ceilf(cm * L_HI);
-  const float d = fmaxf(a.c - newc, -250.0f);             // <= 0 ; -inf on first use
-  const float sc = __builtin_amdgcn_ldexpf(1.0f, (int)d);  // exact power of two
-  a.S0 = (a.S0 + d * a.Z0) * sc; a.Z0 *= sc;
-  a.S1 = (a.S1 + d * a.Z1) * sc; a.Z1 *= sc;
-  a.c = newc; a.negc = -newc;
-  a.thr = (newc + LP_HEADROOM) * (1.0f / L_HI);
+template <int EPC>
+__device__ __forceinline__ Segment make_segment(int V, int split, int cps) {
+  Segment s;
+  const int n_chunks = (V + EPC - 1) / EPC;
+  s.c0 = min(split * cps, n_chunks);
+  s.c1 = min(s.c0 + cps, n_chunks);
+  s.ncell = s.c1 - s.c0;
+  s.tail_valid = V - (n_chunks - 1) * EPC;
+  s.tail_chunk = (s.c1 == n_chunks && s.tail_valid != EPC && s.ncell > 0) ? n_chunks - 1 : -1;
+  return s;
 }
 
-template <int DT, bool MASKED>
-__device__ __forceinline__ void consume_chunk(const uint4& q, LaneAcc& a, typename LogitTraits<DT>::key_t* map,
-                                              int cell, int n_valid) {
-  typedef LogitTraits<DT> T;
-  float x[T::EPC];
-  T::unpack(q, x);
-  if (MASKED) {
-#pragma unroll
-    for (int j = 0; j < T::EPC; ++j) if (j >= n_valid) x[j] = -INFINITY;
-  }
-  float cm = x[0];
-#pragma unroll
-  for (int j = 1; j < T::EPC; ++j) cm = fmaxf(cm, x[j]);
-  if (cm > a.thr) raise_reference(a, cm);
-#pragma unroll
-  for (int j = 0; j < T::EPC; ++j) {
-    const float y = fmaf(x[j], L_LO, fmaf(x[j], L_HI, a.negc));
-    const float e = hw_exp2(y);
-    const float yc = fmaxf(y, -30000.0f);       // -inf logits: 0 * finite = 0 ; NaN still reaches Z through e
-    if (j & 1) { a.Z1 += e; a.S1 = fmaf(e, yc, a.S1); }
-    else       { a.Z0 += e; a.S0 = fmaf(e, yc, a.S0); }
-  }
-  a.M = fmaxf(a.M, cm);
-  map[cell] = T::to_key(cm);
-}
+// ---------------------------------------------------------------------------------------
+// Selection, shared by both paths.
+// ---------------------------------------------------------------------------------------
 
-// grid: rows_launched * nsplit workgroups.  Dynamic LDS: max(cps * sizeof(key_t), LP_ELEM_CAP*8) bytes.
-template <int DT>
-__global__ __launch_bounds__(LP_NT) void k_logits_pass(
-    const void* __restrict__ logits, int64_t row_stride_elems, int V, int K, int F, int rows_per_seq,
-    const int32_t* __restrict__ n_frontier, int nsplit, int cps /* chunks per split */,
-    RowPartial* __restrict__ part, float* __restrict__ part_topv, int32_t* __restrict__ part_topi) {
+// Cells whose key exceeds tau, plus the first `eq_limit` cells (in cell order) whose key equals
+// tau, are written to cell_list.  Returns false (list untouched) if they do not fit.
+template <int DT, int NT>
+__device__ __forceinline__ bool build_cell_list(const typename LogitTraits<DT>::key_t* map, int ncell, float tau,
+                                                int eq_limit, int32_t* cell_list, int32_t (*scan_tmp)[NT / WAVE],
+                                                int* n_cells_out) {
   typedef LogitTraits<DT> T;
-  typedef typename T::key_t key_t;
-  extern __shared__ __align__(16) unsigned char dyn_lds[];
-  key_t* map = (key_t*)dyn_lds;
-  __shared__ double red_d[2][LP_NW];
-  __shared__ float red_f[2][LP_NW];
-  __shared__ uint32_t lane_keys[LP_NT];
-  __shared__ int32_t cell_list[LP_CELL_CAP];
-  __shared__ int32_t scan_tmp[2][LP_NW];
-  __shared__ uint32_t sh_tau;
-  __shared__ int32_t sh_cnt[4];
-
+  constexpr int NW = NT / WAVE;
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
-  const int split = blockIdx.x % nsplit;
-  const int rl = blockIdx.x / nsplit;
-  const int b = rl / rows_per_seq, f = rl % rows_per_seq;
-  if (f >= n_frontier[b]) return;                       // uniform for the workgroup
-  const int64_t row = (int64_t)b * F + f;
-  const int esz = DT == 1 ? 2 : 4;
-  const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * esz);
-
-  const int n_chunks = (V + T::EPC - 1) / T::EPC;
-  const int tail_valid = V - (n_chunks - 1) * T::EPC;  // elements of the last chunk that exist
-  const int c0 = split * cps;
-  int c1 = min(c0 + cps, n_chunks);
-  if (c1 < c0) c1 = c0;
-  const int ncell = c1 - c0;
-  const bool has_tail = (c1 == n_chunks) && (tail_valid != T::EPC) && ncell > 0;
-  const int c1_full = has_tail ? c1 - 1 : c1;
-
-  // ---------------- streaming loop ----------------
-  LaneAcc a;
-  int g = c0 + tid;
-  for (; g + 3 * LP_NT < c1_full; g += 4 * LP_NT) {
-    const uint4 q0 = rowp[g], q1 = rowp[g + LP_NT], q2 = rowp[g + 2 * LP_NT], q3 = rowp[g + 3 * LP_NT];
-    consume_chunk<DT, false>(q0, a, map, g - c0, 0);
-    consume_chunk<DT, false>(q1, a, map, g - c0 + LP_NT, 0);
-    consume_chunk<DT, false>(q2, a, map, g - c0 + 2 * LP_NT, 0);
-    consume_chunk<DT, false>(q3, a, map, g - c0 + 3 * LP_NT, 0);
+  const int cpl = (ncell + NT - 1) / NT;                    // contiguous cells per lane
+  const int s0 = min(tid * cpl, ncell), s1 = min(s0 + cpl, ncell);
+  int n_gt = 0, n_eq = 0;
+#pragma unroll 1
+  for (int s = s0; s < s1; ++s) {
+    const float kv = T::from_key(map[s]);
+    n_gt += kv > tau; n_eq += kv == tau;
   }
-  for (; g < c1_full; g += LP_NT) {
-    const uint4 q0 = rowp[g];
-    consume_chunk<DT, false>(q0, a, map, g - c0, 0);
-  }
-  if (has_tail && ((c1 - 1 - c0) % LP_NT) == tid) {
-    const uint4 q0 = rowp[c1 - 1];
-    consume_chunk<DT, true>(q0, a, map, c1 - 1 - c0, tail_valid);
-  }
-
-  // ---------------- combine the lanes (fp64, exact rescaling) ----------------
-  float cw = wave_max(a.c), mw = wave_max(a.M);
-  if (lane == 0) { red_f[0][wid] = cw; red_f[1][wid] = mw; }
-  lane_keys[tid] = (a.M == -INFINITY && ncell <= tid) ? 0u : sortable_key(a.M);
+  const int ig = wave_scan_incl(n_gt), ie = wave_scan_incl(n_eq);
+  if (lane == WAVE - 1) { scan_tmp[0][wid] = ig; scan_tmp[1][wid] = ie; }
   __syncthreads();
-  float cref = red_f[0][0], mseg = red_f[1][0];
+  int og = 0, oe = 0, tg = 0, te = 0;
 #pragma unroll
-  for (int w = 1; w < LP_NW; ++w) { cref = fmaxf(cref, red_f[0][w]); mseg = fmaxf(mseg, red_f[1][w]); }
-  double Zd = 0.0, Sd = 0.0;
-  {
-    const double Zl = (double)a.Z0 + (double)a.Z1, Sl = (double)a.S0 + (double)a.S1;
-    if (a.c != -INFINITY && Zl != 0.0) {
-      const double dl = fmax((double)a.c - (double)cref, -2000.0);
-      const double sc = ldexp(1.0, (int)dl);
-      Zd = Zl * sc;
-      Sd = (Sl + dl * Zl) * sc;
-    } else {
-      Zd = Zl; Sd = Sl;     // zero, or NaN/inf to be reported
+  for (int w = 0; w < NW; ++w) {
+    if (w < wid) { og += scan_tmp[0][w]; oe += scan_tmp[1][w]; }
+    tg += scan_tmp[0][w]; te += scan_tmp[1][w];
+  }
+  const int take_eq = min(te, eq_limit);
+  const bool fits = tg + take_eq <= SEL_CELL_CAP;
+  if (fits) {
+    int pg = og + ig - n_gt, pe = oe + ie - n_eq;          // exclusive prefixes in cell order
+#pragma unroll 1
+    for (int s = s0; s < s1; ++s) {
+      const float kv = T::from_key(map[s]);
+      if (kv > tau) cell_list[pg++] = s;
+      else if (kv == tau) { if (pe < take_eq) cell_list[tg + pe] = s; ++pe; }
     }
   }
-  Zd = wave_sum(Zd); Sd = wave_sum(Sd);
-  if (lane == 0) { red_d[0][wid] = Zd; red_d[1][wid] = Sd; }
+  __syncthreads();
+  *n_cells_out = tg + take_eq;
+  return fits;
+}
 
-  // ---------------- tau = K-th largest of the lane maxima (wave 0) ----------------
-  if (wid == 0) {
-    uint32_t keys[LP_NW];
+// Re-read the listed cells, keep their elements >= tau, rank them exactly by (logit desc,
+// id asc) and write the best K.  The element list overlays the cell map (no longer needed).
+template <int DT, int NT>
+__device__ __forceinline__ int finish_topk(const uint4* __restrict__ rowp, int c0, int V, int K, float tau,
+                                           const int32_t* cell_list, int n_cells, unsigned char* dyn_lds,
+                                           int32_t* sh_cnt, float* __restrict__ topv, int32_t* __restrict__ topi) {
+  typedef LogitTraits<DT> T;
+  const int tid = threadIdx.x;
+  float* el_v = (float*)dyn_lds;
+  int32_t* el_i = (int32_t*)(dyn_lds + SEL_ELEM_CAP * 4);
+  if (tid == 0) *sh_cnt = 0;
+  int my_cell = -1;
+  uint4 q = make_uint4(0, 0, 0, 0);
+  if (tid < n_cells) { my_cell = c0 + cell_list[tid]; q = rowp[my_cell]; }      // n_cells <= SEL_CELL_CAP <= NT
+  __syncthreads();
+  if (my_cell >= 0) {
+    float x[T::EPC];
+    T::unpack(q, x);
 #pragma unroll
-    for (int v = 0; v < LP_NW; ++v) keys[v] = lane_keys[v * WAVE + lane];
-    const uint32_t tau = wave_kth_largest<LP_NW>(keys, K);
-    if (lane == 0) sh_tau = tau;
+    for (int j = 0; j < T::EPC; ++j) {
+      const int id = my_cell * T::EPC + j;
+      if (id < V && x[j] >= tau) {
+        const int slot = atomicAdd(sh_cnt, 1);
+        el_v[slot] = x[j]; el_i[slot] = id;
+      }
+    }
+  }
+  __syncthreads();
+  const int n_el = *sh_cnt;
+#pragma unroll 1
+  for (int e = tid; e < n_el; e += NT) {
+    const float v = el_v[e]; const int id = el_i[e];
+    int rank = 0;
+#pragma unroll 2
+    for (int o = 0; o < n_el; ++o) {
+      const float vo = el_v[o];
+      rank += (vo > v) || (vo == v && el_i[o] < id);
+    }
+    if (rank < K) { topv[rank] = v; topi[rank] = id; }
+  }
+  return min(n_el, K);
+}
+
+__device__ __forceinline__ RowPartial empty_partial() {
+  RowPartial r;
+  r.ref = -INFINITY; r.a = 0.0; r.Z = 0.0; r.S = 0.0; r.n_top = 0; r.flags = 0u;
+  return r;
+}
+
+// Sum of Z and S over the workgroup in a fixed order (wave butterflies, then waves ascending).
+// Only thread 0 needs the totals: it leaves them in out[0..1] (LDS), so no lane keeps the
+// per-wave partials alive in registers.
+template <int NT>
+__device__ __forceinline__ void block_sum2(double Z, double S, double (*red)[NT / WAVE], double* out) {
+  constexpr int NW = NT / WAVE;
+  Z = wave_sum(Z); S = wave_sum(S);
+  if ((threadIdx.x & (WAVE - 1)) == 0) { red[0][threadIdx.x >> 6] = Z; red[1][threadIdx.x >> 6] = S; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tz = 0.0, ts = 0.0;
+#pragma unroll 1
+    for (int w = 0; w < NW; ++w) { tz += red[0][w]; ts += red[1][w]; }
+    out[0] = tz; out[1] = ts;
+  }
+}
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float* red /*[NT/WAVE]*/) {
+  constexpr int NW = NT / WAVE;
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) t = fmaxf(t, red[w]);
+  return t;
+}
+
+// ---------------------------------------------------------------------------------------
+// Generic path: two passes over the segment, fp64 exponentials.  Any dtype, any values.
+// ---------------------------------------------------------------------------------------
+template <int DT, int NT>
+__device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, const Segment sg,
+                                unsigned char* dyn_lds, RowPartial* __restrict__ part_out,
+                                float* __restrict__ topv, int32_t* __restrict__ topi, uint32_t info_flags) {
+  typedef LogitTraits<DT> T;
+  typedef typename T::key_t key_t;
+  constexpr int NW = NT / WAVE;
+  key_t* map = (key_t*)dyn_lds;
+  __shared__ double red_d[2][NW], sum_d[2];
+  __shared__ float red_f[NW];
+  __shared__ uint32_t lane_keys[NT];
+  __shared__ int32_t cell_list[SEL_CELL_CAP];
+  __shared__ int32_t scan_tmp[2][NW];
+  __shared__ uint32_t sh_tau;
+  __shared__ int32_t sh_cnt, sh_bad;
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  if (tid == 0) sh_bad = 0;
+  __syncthreads();
+
+  // pass 1: cell keys, lane maxima, NaN / +inf
+  float M = -INFINITY;
+  bool bad = false, any = false;
+  for (int g = sg.c0 + tid; g < sg.c1; g += NT) {
+    const uint4 q = rowp[g];
+    float x[T::EPC];
+    T::unpack(q, x);
+    const int nv = (g == sg.tail_chunk) ? sg.tail_valid : T::EPC;
+    float cm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < T::EPC; ++j) {
+      if (j < nv) { bad |= !(x[j] < INFINITY); cm = fmaxf(cm, x[j]); }
+    }
+    M = fmaxf(M, cm);
+    map[g - sg.c0] = T::to_key(cm);
+    any = true;
+  }
+  lane_keys[tid] = any ? sortable_key(M) : 0u;
+  if (bad) sh_bad = 1;
+  const float m = block_max<NT>(M, red_f);          // barriers inside also publish map, lane_keys, sh_bad
+  const bool seg_bad = sh_bad != 0;
+
+  // pass 2: Z = sum e^(x-m), S = sum (x-m) e^(x-m)
+  double Z = 0.0, S = 0.0;
+  if (!seg_bad && m > -INFINITY) {
+    const double md = (double)m;
+    for (int g = sg.c0 + tid; g < sg.c1; g += NT) {
+      const uint4 q = rowp[g];
+      float x[T::EPC];
+      T::unpack(q, x);
+      const int nv = (g == sg.tail_chunk) ? sg.tail_valid : T::EPC;
+#pragma unroll
+      for (int j = 0; j < T::EPC; ++j) {
+        if (j < nv && x[j] > -INFINITY) {
+          const double t = (double)x[j] - md;
+          const double e = exp(t);
+          Z += e;
+          if (e > 0.0) S += t * e;
+        }
+      }
+    }
+  }
+  block_sum2<NT>(Z, S, red_d, sum_d);
+
+  // tau = K-th largest of the lane maxima: a lower bound of the K-th largest logit
+  if (wid == 0) {
+    uint32_t keys[NW];
+#pragma unroll
+    for (int v = 0; v < NW; ++v) keys[v] = lane_keys[v * WAVE + lane];
+    const uint32_t t = wave_kth_largest<NW>(keys, K);
+    if (lane == 0) sh_tau = t;
   }
   __syncthreads();
   uint32_t tau_key = sh_tau;
   float tau = tau_key ? key_to_float(tau_key) : -INFINITY;
-
-  // ---------------- scan the cell map: which cells can hold a top-K element ----------------
-  const int cpl = (ncell + LP_NT - 1) / LP_NT;          // contiguous cells per lane
-  const int s0 = min(tid * cpl, ncell), s1 = min(s0 + cpl, ncell);
-  int n_gt_tot, take_eq;
-  for (int attempt = 0;; ++attempt) {
-    int n_gt = 0, n_eq = 0;
-    for (int s = s0; s < s1; ++s) {
-      const float kv = T::from_key(map[s]);
-      n_gt += kv > tau; n_eq += kv == tau;
-    }
-    const int ig = wave_scan_incl(n_gt), ie = wave_scan_incl(n_eq);
-    if (lane == WAVE - 1) { scan_tmp[0][wid] = ig; scan_tmp[1][wid] = ie; }
-    __syncthreads();
-    int og = 0, oe = 0, tg = 0, te = 0;
-#pragma unroll
-    for (int w = 0; w < LP_NW; ++w) {
-      if (w < wid) { og += scan_tmp[0][w]; oe += scan_tmp[1][w]; }
-      tg += scan_tmp[0][w]; te += scan_tmp[1][w];
-    }
-    n_gt_tot = tg;
-    take_eq = min(te, K);
-    if (tg + take_eq <= LP_CELL_CAP) {
-      int pg = og + ig - n_gt, pe = oe + ie - n_eq;      // exclusive prefixes in cell order
-      for (int s = s0; s < s1; ++s) {
-        const float kv = T::from_key(map[s]);
-        if (kv > tau) cell_list[pg++] = s;
-        else if (kv == tau) { if (pe < take_eq) cell_list[tg + pe] = s; ++pe; }
-      }
-      break;
-    }
-    // Too many cells above the bound (maxima clustered in few lanes): find the exact K-th
-    // largest cell key by radix select over the whole map; then fewer than K cells exceed it.
-    __syncthreads();
+  int n_cells = 0;
+  if (!build_cell_list<DT, NT>(map, sg.ncell, tau, K, cell_list, scan_tmp, &n_cells)) {
+    // Too many cells reach the bound (maxima clustered in few lanes): take the exact K-th
+    // largest cell key by radix select over the whole map; fewer than K cells exceed it.
+    const int cpl = (sg.ncell + NT - 1) / NT;
+    const int s0 = min(tid * cpl, sg.ncell), s1 = min(s0 + cpl, sg.ncell);
     uint32_t prefix = 0, care = 0;
     int k = K;
     for (int bit = 31; bit >= 0; --bit) {
@@ -226,69 +291,259 @@ __global__ __launch_bounds__(LP_NT) void k_logits_pass(
       __syncthreads();
       int tot = 0;
 #pragma unroll
-      for (int w = 0; w < LP_NW; ++w) tot += scan_tmp[0][w];
+      for (int w = 0; w < NW; ++w) tot += scan_tmp[0][w];
       __syncthreads();
       if (tot >= k) prefix = want; else k -= tot;
       care = cmask;
     }
-    tau_key = prefix;
-    tau = tau_key ? key_to_float(tau_key) : -INFINITY;
+    tau = prefix ? key_to_float(prefix) : -INFINITY;
+    build_cell_list<DT, NT>(map, sg.ncell, tau, K, cell_list, scan_tmp, &n_cells);   // now <= 2K-1 cells
   }
-  __syncthreads();
-  const int n_cells = n_gt_tot + take_eq;
+  const int n_top = finish_topk<DT, NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt, topv, topi);
+  if (tid == 0) {
+    RowPartial r;
+    r.ref = (double)m; r.a = (double)m; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = seg_bad ? 0 : n_top; r.flags = (seg_bad ? 1u : 0u) | info_flags;
+    *part_out = r;
+  }
+}
 
-  // ---------------- re-read the candidate cells, keep elements >= tau ----------------
-  // (the element list overlays the cell map, which is no longer needed)
-  float* el_v = (float*)dyn_lds;
-  int32_t* el_i = (int32_t*)(dyn_lds + LP_ELEM_CAP * 4);
-  if (tid == 0) sh_cnt[0] = 0;
-  int my_cell = -1;
-  uint4 q = make_uint4(0, 0, 0, 0);
-  if (tid < n_cells) { my_cell = c0 + cell_list[tid]; q = rowp[my_cell]; }
-  __syncthreads();
-  if (my_cell >= 0) {
-    float x[T::EPC];
-    T::unpack(q, x);
+// grid: rows_launched * nsplit workgroups of NT threads.
+// Dynamic LDS: max(cps * sizeof(key_t), SEL_ELEM_CAP * 8) bytes.
+template <int DT, int NT>
+__global__ __launch_bounds__(NT) void k_logits_generic(
+    const void* __restrict__ logits, int64_t row_stride_elems, int V, int K, int F, int rows_per_seq,
+    const int32_t* __restrict__ n_frontier, int nsplit, int cps, RowPartial* __restrict__ part,
+    float* __restrict__ part_topv, int32_t* __restrict__ part_topi) {
+  typedef LogitTraits<DT> T;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
+  const int b = rl / rows_per_seq, f = rl % rows_per_seq;
+  if (f >= n_frontier[b]) return;                       // uniform for the workgroup
+  const int64_t row = (int64_t)b * F + f;
+  const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * (DT == 1 ? 2 : 4));
+  const Segment sg = make_segment<T::EPC>(V, split, cps);
+  const int64_t po = (int64_t)rl * nsplit + split;      // partial records are indexed by launched row
+  if (sg.ncell == 0) { if (threadIdx.x == 0) part[po] = empty_partial(); return; }
+  generic_segment<DT, NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 0u);
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 fast path: value histogram.
+// ---------------------------------------------------------------------------------------
+constexpr int HP_NT = 1024;
+constexpr int HP_NW = HP_NT / WAVE;
+constexpr int HP_BINS = 8192;                 // sign(1) | exponent mod 32 (5) | mantissa (7)
+constexpr int HP_BPL = HP_BINS / HP_NT;       // bins per lane in the epilogue
+constexpr uint32_t HP_MAG_LO = 102u << 7;     // |x| >= 2^-25
+constexpr uint32_t HP_MAG_SPAN = 32u << 7;    // 32 binades: |x| < 2^7
+
+__device__ __forceinline__ uint32_t hp_bin_of_code(uint32_t code16) {
+  return (code16 & 0xFFFu) | ((code16 >> 3) & 0x1000u);
+}
+// value-ordered rank r in [0, 8192): larger r = larger value.  r -> bf16 code and bin.
+__device__ __forceinline__ uint32_t hp_code_of_rank(int r) {
+  const uint32_t s = r < 4096 ? 1u : 0u;
+  const uint32_t magidx = s ? (uint32_t)(4095 - r) : (uint32_t)(r - 4096);
+  return (s << 15) | (HP_MAG_LO + magidx);
+}
+
+__device__ __forceinline__ int hp_rank_of_code(uint32_t code16) {
+  const int magidx = (int)((code16 & 0x7fffu) - HP_MAG_LO);
+  return (code16 & 0x8000u) ? 4095 - magidx : 4096 + magidx;
+}
+
+// e^v for every value of the window, fp64, in value order (index = rank), so that the 8
+// ranks a lane owns in the epilogue are one contiguous 64-byte read.  Filled once per context.
+__global__ void k_init_exp_table(double* __restrict__ tab_e) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < HP_BINS) tab_e[r] = exp((double)__uint_as_float(hp_code_of_rank(r) << 16));
+}
+
+typedef _Float16 c2t_half2 __attribute__((ext_vector_type(2)));
+typedef unsigned short c2t_ushort2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(c2t_half2, a), __builtin_bit_cast(c2t_half2, b)));
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(c2t_ushort2, a), __builtin_bit_cast(c2t_ushort2, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(c2t_ushort2, a), __builtin_bit_cast(c2t_ushort2, b)));
+}
+
+struct HistLane {
+  uint32_t mag_max = 0u;            // packed running max of |code| (two halves)
+  uint32_t mag_min = 0x7fff7fffu;   // packed running min of |code|
+  float M = -INFINITY;              // running maximum (valid while every logit is in the window)
+};
+
+__device__ __forceinline__ void hist_chunk(const uint4& q, HistLane& a, uint32_t* __restrict__ hist,
+                                           uint16_t* __restrict__ map, int cell) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  // window check on |code|; NaN and infinities have the largest magnitudes
+  uint32_t mx = a.mag_max, mn = a.mag_min;
 #pragma unroll
-    for (int j = 0; j < T::EPC; ++j) {
-      const int id = my_cell * T::EPC + j;
-      if (id < V && x[j] >= tau) {
-        const int slot = atomicAdd(&sh_cnt[0], 1);
-        el_v[slot] = x[j]; el_i[slot] = id;
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t mag = w[j] & 0x7fff7fffu;
+    mx = pk_max_u16(mx, mag); mn = pk_min_u16(mn, mag);
+  }
+  a.mag_max = mx; a.mag_min = mn;
+  // chunk maximum: inside the window bf16 bit patterns order exactly like fp16 bit patterns
+  const uint32_t m2 = pk_max_f16(pk_max_f16(w[0], w[1]), pk_max_f16(w[2], w[3]));
+  const float cm = fmaxf(bf16_lo(m2), bf16_hi(m2));
+  a.M = fmaxf(a.M, cm);
+  map[cell] = (uint16_t)(__float_as_uint(cm) >> 16);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t ih = ((w[j] >> 16) & 0xFFFu) | ((w[j] >> 19) & 0x1000u);
+    const uint32_t il = (w[j] & 0xFFFu) | ((w[j] >> 3) & 0x1000u);
+    atomicAdd(&hist[ih], 1u);
+    atomicAdd(&hist[il], 1u);
+  }
+}
+
+// grid: rows_launched * nsplit workgroups of HP_NT threads.
+// Dynamic LDS: max(cps * 2, SEL_ELEM_CAP * 8) bytes (cell map / element list).
+__global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
+    const void* __restrict__ logits, int64_t row_stride_elems, int V, int K, int F, int rows_per_seq,
+    const int32_t* __restrict__ n_frontier, int nsplit, int cps, const double* __restrict__ tab_e,
+    RowPartial* __restrict__ part, float* __restrict__ part_topv, int32_t* __restrict__ part_topi) {
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  uint16_t* map = (uint16_t*)dyn_lds;
+  __shared__ uint32_t hist[HP_BINS];
+  __shared__ double red_d[2][HP_NW], sum_d[2];
+  __shared__ float red_f[HP_NW];
+  __shared__ uint32_t red_u[2][HP_NW];
+  __shared__ int32_t cell_list[SEL_CELL_CAP];
+  __shared__ int32_t scan_tmp[2][HP_NW];
+  __shared__ int32_t sh_cnt, sh_tau_rank, sh_n_gt;
+
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
+  const int b = rl / rows_per_seq, f = rl % rows_per_seq;
+  if (f >= n_frontier[b]) return;                       // uniform for the workgroup
+  const int64_t row = (int64_t)b * F + f;
+  const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
+  const Segment sg = make_segment<8>(V, split, cps);
+  const int64_t po = (int64_t)rl * nsplit + split;
+  if (sg.ncell == 0) { if (tid == 0) part[po] = empty_partial(); return; }
+
+#pragma unroll
+  for (int j = 0; j < HP_BPL; ++j) hist[tid + j * HP_NT] = 0u;
+  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; }
+  __syncthreads();
+
+  // ---------------- streaming loop: count values, record cell maxima ----------------
+  HistLane a;
+  const int c1_full = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;
+  {
+    int g = sg.c0 + tid;
+    uint4 q = rowp[g < c1_full ? g : sg.c0];            // ncell > 0 whenever a lane enters the loop
+    for (; g < c1_full; g += HP_NT) {
+      const int gn = g + HP_NT;
+      const uint4 qn = rowp[gn < c1_full ? gn : sg.c0]; // prefetch the lane's next chunk
+      hist_chunk(q, a, hist, map, g - sg.c0);
+      q = qn;
+    }
+  }
+  if (sg.tail_chunk >= 0 && ((sg.tail_chunk - sg.c0) % HP_NT) == tid) {
+    const uint4 q = rowp[sg.tail_chunk];                // last chunk of the row: only tail_valid elements exist
+    float x[8];
+    LogitTraits<1>::unpack(q, x);
+    float cm = -INFINITY;
+#pragma unroll 1
+    for (int j = 0; j < sg.tail_valid; ++j) {
+      const uint32_t code = __float_as_uint(x[j]) >> 16, mag = code & 0x7fffu;
+      a.mag_max = pk_max_u16(a.mag_max, mag | (mag << 16));
+      a.mag_min = pk_min_u16(a.mag_min, mag | (mag << 16));
+      cm = fmaxf(cm, x[j]);
+      atomicAdd(&hist[hp_bin_of_code(code)], 1u);
+    }
+    a.M = fmaxf(a.M, cm);
+    map[sg.tail_chunk - sg.c0] = (uint16_t)(__float_as_uint(cm) >> 16);
+  }
+
+  // the lane's slice of the e^v table (ranks 8191-8t-7 ... 8191-8t, ascending): issued now so
+  // that its latency hides behind the reductions below
+  double ev[HP_BPL];
+  {
+    const double* tp = tab_e + (HP_BINS - HP_BPL * (tid + 1));
+#pragma unroll
+    for (int j = 0; j < HP_BPL; ++j) ev[j] = tp[j];
+  }
+
+  // ---------------- is every logit inside the window? ----------------
+  {
+    uint32_t mx = a.mag_max, mn = a.mag_min;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { mx = pk_max_u16(mx, __shfl_xor(mx, o, WAVE)); mn = pk_min_u16(mn, __shfl_xor(mn, o, WAVE)); }
+    if (lane == 0) { red_u[0][wid] = mx; red_u[1][wid] = mn; }
+  }
+  const float m = block_max<HP_NT>(a.M, red_f);         // its barriers also publish hist, map, red_u
+  uint32_t mx = 0u, mn = 0x7fff7fffu;
+#pragma unroll
+  for (int w = 0; w < HP_NW; ++w) { mx = pk_max_u16(mx, red_u[0][w]); mn = pk_min_u16(mn, red_u[1][w]); }
+  const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16), mag_lo = min(mn & 0xffffu, mn >> 16);
+  const bool in_window = sg.ncell > 0 && mag_lo >= HP_MAG_LO && mag_hi < HP_MAG_LO + HP_MAG_SPAN;
+  if (!in_window) {                                     // uniform: rare rows take the exact two-pass path
+    __syncthreads();
+    generic_segment<1, HP_NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 2u);
+    return;
+  }
+
+  // ---------------- epilogue: lane t owns the value ranks 8191-8t ... 8191-8t-7 (descending) ----------------
+  const double md = (double)m;
+  double Z = 0.0, S = 0.0;
+  int lane_total = 0;
+#pragma unroll
+  for (int j = 0; j < HP_BPL; ++j) {
+    const uint32_t code = hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j));
+    const uint32_t n = hist[hp_bin_of_code(code)];
+    lane_total += (int)n;
+    const double t = (double)n * ev[HP_BPL - 1 - j];               // n * e^v (0 for an empty bin)
+    Z += t; S += ((double)__uint_as_float(code << 16) - md) * t;
+    __builtin_amdgcn_sched_barrier(0);                             // one bin at a time: keeps live registers low
+  }
+  block_sum2<HP_NT>(Z, S, red_d, sum_d);
+  // tau = exact K-th largest logit: first rank (from the top) where the running count reaches K
+  {
+    const int incl = wave_scan_incl(lane_total);
+    if (lane == WAVE - 1) scan_tmp[0][wid] = incl;
+    __syncthreads();
+    int above = incl - lane_total;                       // elements in higher-valued lanes
+#pragma unroll
+    for (int w = 0; w < HP_NW; ++w) if (w < wid) above += scan_tmp[0][w];
+    if (above < K && above + lane_total >= K) {          // exactly one lane
+      int run = above;
+#pragma unroll 1
+      for (int j = 0; j < HP_BPL; ++j) {
+        const int r = HP_BINS - 1 - (tid * HP_BPL + j);
+        const int n = (int)hist[hp_bin_of_code(hp_code_of_rank(r))];
+        if (run < K && run + n >= K) { sh_tau_rank = r; sh_n_gt = run; }
+        run += n;
       }
     }
+    __syncthreads();
   }
-  __syncthreads();
-  const int n_el = sh_cnt[0];
-  const int n_top = min(n_el, K);
-
-  // ---------------- exact ranking of the few candidates ----------------
-  const int64_t po = (int64_t)rl * nsplit + split;      // partial records are indexed by launched row
-  for (int e = tid; e < n_el; e += LP_NT) {
-    const float v = el_v[e]; const int id = el_i[e];
-    int rank = 0;
-    for (int o = 0; o < n_el; ++o) {
-      const float vo = el_v[o];
-      rank += (vo > v) || (vo == v && el_i[o] < id);
-    }
-    if (rank < K) { part_topv[po * K + rank] = v; part_topi[po * K + rank] = id; }
-  }
+  float tau = -INFINITY;
+  int eq_limit = K;
+  if (sh_tau_rank >= 0) { tau = __uint_as_float(hp_code_of_rank(sh_tau_rank) << 16); eq_limit = K - sh_n_gt; }
+  int n_cells = 0;
+  build_cell_list<1, HP_NT>(map, sg.ncell, tau, eq_limit, cell_list, scan_tmp, &n_cells);  // <= K cells: always fits
+  const int n_top = finish_topk<1, HP_NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt,
+                                          part_topv + po * K, part_topi + po * K);
   if (tid == 0) {
-    double Zt = 0.0, St = 0.0;
-#pragma unroll
-    for (int w = 0; w < LP_NW; ++w) { Zt += red_d[0][w]; St += red_d[1][w]; }
     RowPartial r;
-    r.Z = Zt; r.S2 = St; r.c = cref; r.m = mseg; r.n_top = n_top;
-    r.flags = (Zt != Zt || Zt == INFINITY || St != St) ? 1u : 0u;
+    r.ref = md; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
     part[po] = r;
   }
 }
 
 // Plain streaming read: the practical HBM ceiling.
-__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ p, size_t n16, uint32_t* out) {
+__global__ __launch_bounds__(1024) void k_stream_read(const uint4* __restrict__ p, size_t n16, uint32_t* out) {
   uint32_t acc = 0;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 1024;
   for (; i + 3 * stride < n16; i += 4 * stride) {
     const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
     acc += a.x ^ a.y ^ a.z ^ a.w; acc += b.x ^ b.y ^ b.z ^ b.w;

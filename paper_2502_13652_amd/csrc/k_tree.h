@@ -69,35 +69,36 @@ __global__ __launch_bounds__(1024) void k_score_prune(
   int32_t* ctok = (int32_t*)(cz + FK);
   int32_t* surv = ctok + FK;
   float* cP = (float*)(surv + FK);
-  __shared__ double rowZ[SP_MAX_F];
-  __shared__ float rowC[SP_MAX_F], rowH[SP_MAX_F], parP[SP_MAX_F];
+  __shared__ double rowZ[SP_MAX_F], rowC[SP_MAX_F];
+  __shared__ float rowH[SP_MAX_F], parP[SP_MAX_F];
   __shared__ int32_t rowBad[SP_MAX_F], parNode[SP_MAX_F];
-  __shared__ int32_t n_surv, any_bad;
+  __shared__ int32_t n_surv, any_bad, any_slow;
 
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int nf = s.n_frontier[b];
   const int nn = s.n_nodes[b];
   for (int i = tid; i < 5 * h + 1; i += nt) w[i] = s.cls[i];
-  if (tid == 0) { n_surv = 0; any_bad = 0; }
+  if (tid == 0) { n_surv = 0; any_bad = 0; any_slow = 0; }
+  __syncthreads();
 
-  // ---- per row: merge the splits (exact power-of-two rescaling, fp64), entropy ----
+  // ---- per row: merge the splits (fp64), entropy of Eq. 2 ----
   if (tid < nf) {
     const RowPartial* rp = part + ((int64_t)b * rows_per_seq + tid) * nsplit;
-    float c = -INFINITY; uint32_t fl = 0;
-    for (int q = 0; q < nsplit; ++q) { c = fmaxf(c, rp[q].c); fl |= rp[q].flags; }
-    double Z = 0.0, S2 = 0.0;
+    double R = -INFINITY; uint32_t fl = 0;
+    for (int q = 0; q < nsplit; ++q) { R = fmax(R, rp[q].ref); fl |= rp[q].flags & 1u; if (rp[q].flags & 2u) any_slow = 1; }
+    double Z = 0.0, S = 0.0;
     for (int q = 0; q < nsplit; ++q) {
       const double Zq = rp[q].Z;
-      if (rp[q].c != -INFINITY && Zq != 0.0) {
-        const double dl = fmax((double)rp[q].c - (double)c, -2000.0);
-        const double sc = ldexp(1.0, (int)dl);
-        Z += Zq * sc; S2 += (rp[q].S2 + dl * Zq) * sc;
+      if (Zq > 0.0 && rp[q].ref > -INFINITY) {
+        const double da = rp[q].a - R, dl = rp[q].ref - R;   // dl <= 0
+        const double sc = da == 0.0 ? 1.0 : exp(da);
+        Z += Zq * sc; S += (rp[q].S + dl * Zq) * sc;
       }
     }
-    const bool bad = fl != 0 || !(Z > 0.0) || c == -INFINITY || c == INFINITY;
-    // p_j = 2^(y_j)/Z with y_j = x_j*log2(e) - c  =>  H = ln Z - ln2 * S2 / Z
-    const double H = bad ? 0.0 : log(Z) - LN2 * S2 / Z;
-    rowZ[tid] = Z; rowC[tid] = c; rowH[tid] = (float)H; rowBad[tid] = bad;
+    const bool bad = fl != 0 || !(Z > 0.0) || !(R > -INFINITY) || !(R < INFINITY);
+    // p_j = e^(x_j - R) / Z  =>  H = -sum p ln p = ln Z - S / Z
+    const double H = bad ? 0.0 : log(Z) - S / Z;
+    rowZ[tid] = Z; rowC[tid] = R; rowH[tid] = (float)H; rowBad[tid] = bad;
     parP[tid] = s.fr_P[(int64_t)b * F + tid];
     parNode[tid] = s.fr_node[(int64_t)b * F + tid];
     if (bad) any_bad = 1;
@@ -143,8 +144,7 @@ __global__ __launch_bounds__(1024) void k_score_prune(
     {
       const float x = cz[i]; const int id = ctok[i];
       if (id >= 0) {
-        const double y = (double)x * L2E - (double)rowC[f];
-        p32 = (float)(exp2(y) / rowZ[f]);
+        p32 = (float)(exp((double)x - rowC[f]) / rowZ[f]);
         P32 = parP[f] * p32;
         z = mlp_logit(w, h, P32, rowH[f], (float)layer);
         tok = id;
@@ -197,6 +197,7 @@ __global__ __launch_bounds__(1024) void k_score_prune(
     s.n_frontier[b] = n_keep;
     s.n_cand[b] = ncand;
     if (any_bad) s.status[b] |= 1u;
+    if (any_slow) s.status[b] |= 2u;
     if (n_keep) atomicAdd(&s.layer_rows[layer + 1], n_keep);
   }
 }

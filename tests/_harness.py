@@ -64,7 +64,7 @@ def compare_final(go, oo, seqs, tag):
         for k in ("tokens", "parent", "position"):
             np.testing.assert_array_equal(go[k][b], oo[k][i], err_msg="%s seq %d %s" % (tag, b, k))
         np.testing.assert_array_equal(go["mask"][b], oo["mask"][i], err_msg="%s seq %d mask" % (tag, b))
-        assert int(go["status"][b]) == int(oo["status"][i])
+        assert int(go["status"][b]) & 1 == int(oo["status"][i])      # bit 1 is informational (slow path taken)
         for k in ("conf", "joint_prob", "entropy"):
             ok = close(go[k][b], oo[k][i], atol=1e-30)
             assert ok.all(), "%s seq %d %s" % (tag, b, k)

@@ -64,7 +64,12 @@ def test_rows_against_oracle(dtype, V, K, splits):
     W1 = np.zeros((h, 3), np.float32); W1[0, 0] = 1
     ctx.set_classifier(W1, np.zeros(h, np.float32), np.array([1, 0], np.float32), 0.0)
     if splits:
-        ctx.set_row_splits(splits, splits)
+        from paper_2502_13652_amd import C2TError
+        try:
+            ctx.set_row_splits(splits, splits)
+        except C2TError as e:
+            assert e.code == -2          # this split would not fit the cell map in LDS
+            pytest.skip("split count below the minimum for this vocabulary and dtype")
     print("rows V=%d K=%d %s splits=%d" % (V, K, dtype, splits), flush=True)
     ctx.reset()
     ctx.expand_layer(xd)
@@ -79,7 +84,9 @@ def test_rows_against_oracle(dtype, V, K, splits):
         np.testing.assert_array_equal(c["token"][b, :k], r["ids"], err_msg=name)
         ok = close(c["p"][b, :k], r["p"].astype(np.float32), atol=1e-37)
         assert ok.all(), "%s p: %s vs %s" % (name, c["p"][b, :k][~ok][:3], r["p"][~ok][:3])
-        assert close(c["H"][b, 0], np.float32(r["H"]), atol=2e-6 * RTOL / 1e-5).all(), "%s H: %g vs %g" % (name, c["H"][b, 0], r["H"])
+        # absolute floor: the oracle adds V terms one by one in fp64, so its Z (and with it H = ln Z - S/Z)
+        # carries up to V * 2^-53 of rounding; only rows with H below ~1e-5 ever get near it
+        assert close(c["H"][b, 0], np.float32(r["H"]), atol=V * 2.0 ** -53).all(), "%s H: %g vs %g" % (name, c["H"][b, 0], r["H"])
         assert (c["z"][b, :k] == c["P"][b, :k]).all() and (c["P"][b, :k] == c["p"][b, :k]).all()
 
 
@@ -103,6 +110,6 @@ def test_bad_rows_set_status_and_yield_nothing(dtype):
         ctx.expand_layer(x)
         out = to_np(ctx.finalize_tree())
         torch.cuda.synchronize()
-        np.testing.assert_array_equal(out["status"], [0, 1, 1, 1, 0])
+        np.testing.assert_array_equal(out["status"] & 1, [0, 1, 1, 1, 0])
         np.testing.assert_array_equal(out["n_nodes"], [1, 0, 0, 0, 1])
         assert (out["tokens"][1:4] == -1).all() and not out["mask"][1:4].any()

@@ -26,7 +26,7 @@ constexpr int MAX_MAP_BYTES_BF16 = 40 * 1024;
 constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
 constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
 constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
-constexpr int TARGET_WORKGROUPS = 2048;        // enough to fill 256 CUs several times over
+constexpr int TARGET_WORKGROUPS = 512;         // two workgroups per CU; beyond that a split only adds epilogues
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 

@@ -8,11 +8,11 @@ namespace c2t {
 constexpr int WAVE = 64;
 
 // Per (row, split) result of the logits pass: Z = sum_j e^(x_j - a), S = sum_j (x_j - ref) e^(x_j - a),
-// both fp64, where ref is the segment's largest logit and the exponent offset a is ref (two-pass path)
-// or 0 (histogram path, whose table holds e^v itself).
+// both fp64, where ref is the segment's largest logit and the exponent offset a is ref (two-pass
+// path) or 0 (histogram path, whose table holds e^v itself).
 struct __attribute__((aligned(16))) RowPartial {
   double ref;     // largest logit of the segment (exact); -inf for an empty or all -inf segment
-  double a;       // exponent offset of the sums
+  double a;       // offset of the sums
   double Z;
   double S;
   int32_t n_top;  // entries of the segment's top list that are valid (<= K)

@@ -372,23 +372,49 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 }
 
 struct HistLane {
-  uint32_t mag_max = 0u;            // packed running max of |code| (two halves)
-  uint32_t mag_min = 0x7fff7fffu;   // packed running min of |code|
-  float M = -INFINITY;              // running maximum (valid while every logit is in the window)
+  uint32_t mag_max = 0u;            // packed running max of |code| (two halves): NaN, inf and |x| >= 2^7 show here
+  float M = -INFINITY;              // running maximum
+  int n_tiny = 0;                   // logits with |x| < 2^-25 (zeros included): e^x = 1 + x to fp64 accuracy
+  double s_tiny = 0.0;              // their sum
 };
+
+// One element at a time: used for chunks that hold a logit below the window and for a row's
+// partial last chunk.
+__device__ __forceinline__ void hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist,
+                                              uint16_t* __restrict__ map, int cell) {
+  float x[8];
+  LogitTraits<1>::unpack(q, x);
+  float cm = -INFINITY;
+#pragma unroll 1
+  for (int j = 0; j < n_valid; ++j) {
+    const uint32_t code = __float_as_uint(x[j]) >> 16, mag = code & 0x7fffu;
+    a.mag_max = pk_max_u16(a.mag_max, mag);
+    cm = fmaxf(cm, x[j]);
+    if (mag < HP_MAG_LO) { a.n_tiny += 1; a.s_tiny += (double)x[j]; }
+    else atomicAdd(&hist[hp_bin_of_code(code)], 1u);
+  }
+  a.M = fmaxf(a.M, cm);
+  map[cell] = (uint16_t)(__float_as_uint(cm) >> 16);
+}
 
 __device__ __forceinline__ void hist_chunk(const uint4& q, HistLane& a, uint32_t* __restrict__ hist,
                                            uint16_t* __restrict__ map, int cell) {
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-  // window check on |code|; NaN and infinities have the largest magnitudes
-  uint32_t mx = a.mag_max, mn = a.mag_min;
+  // |code| range of the chunk; NaN and infinities have the largest magnitudes
+  uint32_t mx = a.mag_max, mn = 0x7fff7fffu;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t mag = w[j] & 0x7fff7fffu;
     mx = pk_max_u16(mx, mag); mn = pk_min_u16(mn, mag);
   }
-  a.mag_max = mx; a.mag_min = mn;
+  a.mag_max = mx;
+  constexpr uint32_t LO2 = HP_MAG_LO | (HP_MAG_LO << 16);
+  if (pk_min_u16(mn, LO2) != LO2) {           // rare: a logit below the window
+    hist_elements(q, 8, a, hist, map, cell);
+    return;
+  }
   // chunk maximum: inside the window bf16 bit patterns order exactly like fp16 bit patterns
+  // (above it the row leaves this path anyway)
   const uint32_t m2 = pk_max_f16(pk_max_f16(w[0], w[1]), pk_max_f16(w[2], w[3]));
   const float cm = fmaxf(bf16_lo(m2), bf16_hi(m2));
   a.M = fmaxf(a.M, cm);
@@ -412,11 +438,13 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   uint16_t* map = (uint16_t*)dyn_lds;
   __shared__ uint32_t hist[HP_BINS];
   __shared__ double red_d[2][HP_NW], sum_d[2];
-  __shared__ float red_f[HP_NW];
-  __shared__ uint32_t red_u[2][HP_NW];
+  __shared__ float red_f[HP_NW], red_v[HP_NW];
+  __shared__ uint32_t red_u[HP_NW];
+  __shared__ int32_t sh_ntiny;
+  __shared__ double sh_stiny;
   __shared__ int32_t cell_list[SEL_CELL_CAP];
   __shared__ int32_t scan_tmp[2][HP_NW];
-  __shared__ int32_t sh_cnt, sh_tau_rank, sh_n_gt;
+  __shared__ int32_t sh_cnt, sh_ncell, sh_tau_rank, sh_n_gt;
 
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
   const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
@@ -430,86 +458,113 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
 
 #pragma unroll
   for (int j = 0; j < HP_BPL; ++j) hist[tid + j * HP_NT] = 0u;
-  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; }
+  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_ntiny = 0; sh_stiny = 0.0; }
   __syncthreads();
 
   // ---------------- streaming loop: count values, record cell maxima ----------------
   HistLane a;
   const int c1_full = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;
   {
+    // four chunks per lane in flight: a workgroup that streams alone (its neighbour on the CU is
+    // in its epilogue) still covers the HBM latency.  Unrolled by four so that each buffer is
+    // refilled right after it has been counted, without register copies.
     int g = sg.c0 + tid;
-    uint4 q = rowp[g < c1_full ? g : sg.c0];            // ncell > 0 whenever a lane enters the loop
-    for (; g < c1_full; g += HP_NT) {
-      const int gn = g + HP_NT;
-      const uint4 qn = rowp[gn < c1_full ? gn : sg.c0]; // prefetch the lane's next chunk
-      hist_chunk(q, a, hist, map, g - sg.c0);
-      q = qn;
+    const uint4* dummy = rowp + sg.c0;                   // in-bounds address for lanes past their last chunk
+#define C2T_LOAD(i) (*((i) < c1_full ? rowp + (i) : dummy))
+    uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + HP_NT), qc = C2T_LOAD(g + 2 * HP_NT), qd = C2T_LOAD(g + 3 * HP_NT);
+    for (; g + 3 * HP_NT < c1_full; g += 4 * HP_NT) {    // whole groups of four: one straight-line body
+      hist_chunk(qa, a, hist, map, g - sg.c0);
+      qa = C2T_LOAD(g + 4 * HP_NT);
+      hist_chunk(qb, a, hist, map, g + HP_NT - sg.c0);
+      qb = C2T_LOAD(g + 5 * HP_NT);
+      hist_chunk(qc, a, hist, map, g + 2 * HP_NT - sg.c0);
+      qc = C2T_LOAD(g + 6 * HP_NT);
+      hist_chunk(qd, a, hist, map, g + 3 * HP_NT - sg.c0);
+      qd = C2T_LOAD(g + 7 * HP_NT);
     }
+    if (g < c1_full) hist_chunk(qa, a, hist, map, g - sg.c0);                           // up to three left
+    if (g + HP_NT < c1_full) hist_chunk(qb, a, hist, map, g + HP_NT - sg.c0);
+    if (g + 2 * HP_NT < c1_full) hist_chunk(qc, a, hist, map, g + 2 * HP_NT - sg.c0);
+#undef C2T_LOAD
   }
-  if (sg.tail_chunk >= 0 && ((sg.tail_chunk - sg.c0) % HP_NT) == tid) {
-    const uint4 q = rowp[sg.tail_chunk];                // last chunk of the row: only tail_valid elements exist
-    float x[8];
-    LogitTraits<1>::unpack(q, x);
-    float cm = -INFINITY;
-#pragma unroll 1
-    for (int j = 0; j < sg.tail_valid; ++j) {
-      const uint32_t code = __float_as_uint(x[j]) >> 16, mag = code & 0x7fffu;
-      a.mag_max = pk_max_u16(a.mag_max, mag | (mag << 16));
-      a.mag_min = pk_min_u16(a.mag_min, mag | (mag << 16));
-      cm = fmaxf(cm, x[j]);
-      atomicAdd(&hist[hp_bin_of_code(code)], 1u);
-    }
-    a.M = fmaxf(a.M, cm);
-    map[sg.tail_chunk - sg.c0] = (uint16_t)(__float_as_uint(cm) >> 16);
-  }
+  if (sg.tail_chunk >= 0 && ((sg.tail_chunk - sg.c0) % HP_NT) == tid)    // only tail_valid elements exist
+    hist_elements(rowp[sg.tail_chunk], sg.tail_valid, a, hist, map, sg.tail_chunk - sg.c0);
+  if (a.n_tiny) { atomicAdd(&sh_ntiny, a.n_tiny); atomicAdd(&sh_stiny, a.s_tiny); }
 
   // the lane's slice of the e^v table (ranks 8191-8t-7 ... 8191-8t, ascending): issued now so
-  // that its latency hides behind the reductions below
+  // that its latency hides behind the first barrier
   double ev[HP_BPL];
   {
     const double* tp = tab_e + (HP_BINS - HP_BPL * (tid + 1));
 #pragma unroll
     for (int j = 0; j < HP_BPL; ++j) ev[j] = tp[j];
   }
-
-  // ---------------- is every logit inside the window? ----------------
+  // per-wave: magnitude range and maximum
   {
-    uint32_t mx = a.mag_max, mn = a.mag_min;
+    uint32_t mx = a.mag_max;
+    float mw = a.M;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { mx = pk_max_u16(mx, __shfl_xor(mx, o, WAVE)); mn = pk_min_u16(mn, __shfl_xor(mn, o, WAVE)); }
-    if (lane == 0) { red_u[0][wid] = mx; red_u[1][wid] = mn; }
+    for (int o = 32; o > 0; o >>= 1) {
+      mx = pk_max_u16(mx, __shfl_xor(mx, o, WAVE));
+      mw = fmaxf(mw, __shfl_xor(mw, o, WAVE));
+    }
+    if (lane == 0) { red_u[wid] = mx; red_f[wid] = mw; }
   }
-  const float m = block_max<HP_NT>(a.M, red_f);         // its barriers also publish hist, map, red_u
-  uint32_t mx = 0u, mn = 0x7fff7fffu;
-#pragma unroll
-  for (int w = 0; w < HP_NW; ++w) { mx = pk_max_u16(mx, red_u[0][w]); mn = pk_min_u16(mn, red_u[1][w]); }
-  const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16), mag_lo = min(mn & 0xffffu, mn >> 16);
-  const bool in_window = sg.ncell > 0 && mag_lo >= HP_MAG_LO && mag_hi < HP_MAG_LO + HP_MAG_SPAN;
-  if (!in_window) {                                     // uniform: rare rows take the exact two-pass path
-    __syncthreads();
-    generic_segment<1, HP_NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 2u);
-    return;
-  }
+  __syncthreads();                                     // histogram, cell map and wave results complete
 
-  // ---------------- epilogue: lane t owns the value ranks 8191-8t ... 8191-8t-7 (descending) ----------------
-  const double md = (double)m;
+  // ---------------- lane t owns the value ranks 8191-8t ... 8191-8t-7 (descending) ----------------
+  // Z = sum n_v e^v and S = sum n_v (v - m) e^v.  S is accumulated against the largest value seen
+  // so far at each level (lane, wave, workgroup), so every term has the same sign and nothing
+  // cancels: rows whose entropy is tiny keep their relative accuracy.
   double Z = 0.0, S = 0.0;
   int lane_total = 0;
+  float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
+  {
+    uint32_t n[HP_BPL];
 #pragma unroll
-  for (int j = 0; j < HP_BPL; ++j) {
-    const uint32_t code = hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j));
-    const uint32_t n = hist[hp_bin_of_code(code)];
-    lane_total += (int)n;
-    const double t = (double)n * ev[HP_BPL - 1 - j];               // n * e^v (0 for an empty bin)
-    Z += t; S += ((double)__uint_as_float(code << 16) - md) * t;
-    __builtin_amdgcn_sched_barrier(0);                             // one bin at a time: keeps live registers low
+    for (int j = 0; j < HP_BPL; ++j) {
+      n[j] = hist[hp_bin_of_code(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)))];
+      lane_total += (int)n[j];
+    }
+#pragma unroll
+    for (int j = HP_BPL - 1; j >= 0; --j)
+      if (n[j]) vtop = __uint_as_float(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)) << 16);
+    const double vt = lane_total ? (double)vtop : 0.0;
+#pragma unroll
+    for (int j = 0; j < HP_BPL; ++j) {
+      const double v = (double)__uint_as_float(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)) << 16);
+      const double t = (double)n[j] * ev[HP_BPL - 1 - j];          // n * e^v (0 for an empty bin)
+      Z += t; S += (v - vt) * t;
+      __builtin_amdgcn_sched_barrier(0);                           // one bin at a time: keeps live registers low
+    }
   }
-  block_sum2<HP_NT>(Z, S, red_d, sum_d);
+  const float vw = wave_max(vtop);                      // -inf only if the whole wave owns empty bins
+  if (lane_total) S += ((double)vtop - (double)vw) * Z;
+  Z = wave_sum(Z); S = wave_sum(S);
+  const int incl = wave_scan_incl(lane_total);
+  if (lane == 0) { red_d[0][wid] = Z; red_d[1][wid] = S; red_v[wid] = vw; }
+  if (lane == WAVE - 1) scan_tmp[0][wid] = incl;
+  __syncthreads();
+
+  uint32_t mx = 0u;
+  float m = red_f[0];
+#pragma unroll
+  for (int w = 0; w < HP_NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m = fmaxf(m, red_f[w]); }
+  const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16);
+  const int n_tiny = sh_ntiny;
+  if (tid == 0) {                                       // fixed order: waves ascending
+    double tz = 0.0, ts = 0.0;
+#pragma unroll 1
+    for (int w = 0; w < HP_NW; ++w)
+      if (red_d[0][w] > 0.0) { tz += red_d[0][w]; ts += red_d[1][w] + ((double)red_v[w] - (double)m) * red_d[0][w]; }
+    if (n_tiny) {                                       // e^x = 1 + x, x e^x = x for |x| < 2^-25
+      const double zt = (double)n_tiny + sh_stiny;
+      tz += zt; ts += sh_stiny - (double)m * zt;
+    }
+    sum_d[0] = tz; sum_d[1] = ts;
+  }
   // tau = exact K-th largest logit: first rank (from the top) where the running count reaches K
   {
-    const int incl = wave_scan_incl(lane_total);
-    if (lane == WAVE - 1) scan_tmp[0][wid] = incl;
-    __syncthreads();
     int above = incl - lane_total;                       // elements in higher-valued lanes
 #pragma unroll
     for (int w = 0; w < HP_NW; ++w) if (w < wid) above += scan_tmp[0][w];
@@ -523,18 +578,42 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
         run += n;
       }
     }
+  }
+  __syncthreads();
+  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, infinities, NaN), or if
+  // logits below it exist and the K-th largest logit is not a positive window value (then they
+  // could be among the top K, which the histogram cannot rank).
+  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || (n_tiny > 0 && sh_tau_rank < HP_BINS / 2)) {
     __syncthreads();
+    generic_segment<1, HP_NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 2u);
+    return;
   }
   float tau = -INFINITY;
   int eq_limit = K;
   if (sh_tau_rank >= 0) { tau = __uint_as_float(hp_code_of_rank(sh_tau_rank) << 16); eq_limit = K - sh_n_gt; }
-  int n_cells = 0;
-  build_cell_list<1, HP_NT>(map, sg.ncell, tau, eq_limit, cell_list, scan_tmp, &n_cells);  // <= K cells: always fits
+
+  // ---------------- cells that can hold a top-K element ----------------
+  // Only a lane whose own maximum reaches tau owns such a cell (its cells are tid, tid+NT, ...).
+  // Fewer than K cells exceed tau; cells equal to tau are all taken when they fit (the exact
+  // ranking below keeps the lowest ids), else the ordered scan picks the first eq_limit of them.
+  if (a.M >= tau) {
+#pragma unroll 1
+    for (int cix = tid; cix < sg.ncell; cix += HP_NT) {
+      if (__uint_as_float((uint32_t)map[cix] << 16) >= tau) {
+        const int slot = atomicAdd(&sh_ncell, 1);
+        if (slot < SEL_CELL_CAP) cell_list[slot] = cix;
+      }
+    }
+  }
+  __syncthreads();
+  int n_cells = sh_ncell;
+  if (n_cells > SEL_CELL_CAP)                            // massive ties at tau
+    build_cell_list<1, HP_NT>(map, sg.ncell, tau, eq_limit, cell_list, scan_tmp, &n_cells);
   const int n_top = finish_topk<1, HP_NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt,
                                           part_topv + po * K, part_topi + po * K);
   if (tid == 0) {
     RowPartial r;
-    r.ref = md; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
+    r.ref = (double)m; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
     part[po] = r;
   }
 }

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(1024) void k_score_prune(
     for (int q = 0; q < nsplit; ++q) {
       const double Zq = rp[q].Z;
       if (Zq > 0.0 && rp[q].ref > -INFINITY) {
-        const double da = rp[q].a - R, dl = rp[q].ref - R;   // dl <= 0
+        const double da = rp[q].a - R, dl = rp[q].ref - R;   // re-reference to the row maximum R; dl <= 0
         const double sc = da == 0.0 ? 1.0 : exp(da);
         Z += Zq * sc; S += (rp[q].S + dl * Zq) * sc;
       }
@@ -116,22 +116,53 @@ __global__ __launch_bounds__(1024) void k_score_prune(
       if (!rowBad[f] && r < part[base].n_top) { cz[i] = part_topv[base * K + r]; ctok[i] = part_topi[base * K + r]; }
     }
   } else {
-    // an entry's merged rank = number of entries of the row's other lists (and its own) ahead of it
+    // An entry's merged rank = number of entries of the row's lists ahead of it.  Rows are taken
+    // in groups whose lists fit the staging area (surv/cP are free until the scoring step).
+    float* sv = (float*)surv; int32_t* si = (int32_t*)cP;
     const int per_row = nsplit * K;
-    for (int ent = tid; ent < nf * per_row; ent += nt) {
-      const int f = ent / per_row, q = (ent % per_row) / K, e = ent % K;
-      const int64_t base = ((int64_t)b * rows_per_seq + f) * nsplit;
-      if (rowBad[f] || e >= part[base + q].n_top) continue;
-      const float v = part_topv[(base + q) * K + e]; const int vi = part_topi[(base + q) * K + e];
-      int ahead = 0;
-      for (int q2 = 0; q2 < nsplit; ++q2) {
-        const int n2 = part[base + q2].n_top;
-        for (int e2 = 0; e2 < n2; ++e2) {
-          const float v2 = part_topv[(base + q2) * K + e2];
-          ahead += (v2 > v) || (v2 == v && part_topi[(base + q2) * K + e2] < vi);
+    const int rows_per_group = max(1, FK / per_row);       // staging holds FK entries
+    for (int f0 = 0; f0 < nf; f0 += rows_per_group) {
+      const int nr = min(rows_per_group, nf - f0);
+      if (per_row <= FK) {
+        for (int ent = tid; ent < nr * per_row; ent += nt) {
+          const int f = f0 + ent / per_row, q = (ent % per_row) / K, e = ent % K;
+          const int64_t base = ((int64_t)b * rows_per_seq + f) * nsplit;
+          const bool ok = !rowBad[f] && e < part[base + q].n_top;
+          sv[ent] = ok ? part_topv[(base + q) * K + e] : 0.f;
+          si[ent] = ok ? part_topi[(base + q) * K + e] : -1;
+        }
+        __syncthreads();
+        for (int ent = tid; ent < nr * per_row; ent += nt) {
+          const int vi = si[ent];
+          if (vi < 0) continue;
+          const float v = sv[ent];
+          const int r0 = (ent / per_row) * per_row;
+          int ahead = 0;
+          for (int o = r0; o < r0 + per_row; ++o) {
+            const int oi = si[o];
+            ahead += oi >= 0 && ((sv[o] > v) || (sv[o] == v && oi < vi));
+          }
+          if (ahead < K) { const int f = f0 + ent / per_row; cz[f * K + ahead] = v; ctok[f * K + ahead] = vi; }
+        }
+        __syncthreads();
+      } else {
+        // one row's lists exceed the staging area (very many splits): rank from global memory
+        for (int ent = tid; ent < per_row; ent += nt) {
+          const int f = f0, q = ent / K, e = ent % K;
+          const int64_t base = ((int64_t)b * rows_per_seq + f) * nsplit;
+          if (rowBad[f] || e >= part[base + q].n_top) continue;
+          const float v = part_topv[(base + q) * K + e]; const int vi = part_topi[(base + q) * K + e];
+          int ahead = 0;
+          for (int q2 = 0; q2 < nsplit; ++q2) {
+            const int n2 = part[base + q2].n_top;
+            for (int e2 = 0; e2 < n2; ++e2) {
+              const float v2 = part_topv[(base + q2) * K + e2];
+              ahead += (v2 > v) || (v2 == v && part_topi[(base + q2) * K + e2] < vi);
+            }
+          }
+          if (ahead < K) { cz[f * K + ahead] = v; ctok[f * K + ahead] = vi; }
         }
       }
-      if (ahead < K) { cz[f * K + ahead] = v; ctok[f * K + ahead] = vi; }
     }
   }
   __syncthreads();

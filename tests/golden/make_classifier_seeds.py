@@ -4,7 +4,8 @@ A random 3->h->1 MLP drawn N(0, 0.5) is often degenerate as a pruning classifier
 every candidate or none).  Rule, fixed before any GPU run: for each config take the smallest
 seed s >= 0 for which the oracle, run on the first min(B, 4) sequences of workload instance 0,
   (a) lets between 20% and 80% of the second layer's candidates pass the threshold beta, and
-  (b) ends every one of those sequences with at least half of the node budget used.
+  (b) builds, for every one of those sequences, a tree that uses the whole node budget or is still
+      growing in the last layer (so the workload exercises every layer, not a tree that dies early).
 Usage: python tests/golden/make_classifier_seeds.py
 """
 import json
@@ -35,8 +36,9 @@ def evaluate(cfg, seed, logits):
             tot = int(c["n_cand"].sum())
             surv = sum(int((c["z"][b, :c["n_cand"][b]] > zb).sum()) for b in range(ns))
             frac = surv / max(tot, 1)
+    alive = t.frontier()["n_frontier"].tolist() if t.layer == cfg["D"] else [0] * ns
     out = t.finalize()
-    return frac, out["n_nodes"].tolist()
+    return frac, out["n_nodes"].tolist(), alive
 
 
 def main():
@@ -44,10 +46,10 @@ def main():
     for name, cfg in W.CONFIGS.items():
         ns = min(cfg["B"], 4)
         logits = [W.as_numpy_bits(W.logits_layer(cfg, l, seqs=range(ns))) for l in range(cfg["D"])]
-        for seed in range(200):
-            frac, nn = evaluate(cfg, seed, logits)
-            ok = frac is not None and 0.2 <= frac <= 0.8 and min(nn) >= cfg["N"] / 2
-            print(name, seed, frac, nn, "OK" if ok else "", flush=True)
+        for seed in range(2000):
+            frac, nn, alive = evaluate(cfg, seed, logits)
+            ok = frac is not None and 0.2 <= frac <= 0.8 and all(n == cfg["N"] or a > 0 for n, a in zip(nn, alive))
+            print(name, seed, frac, nn, alive, "OK" if ok else "", flush=True)
             if ok:
                 result[name] = dict(seed=seed, layer1_pass_fraction=frac, n_nodes=nn)
                 break

@@ -39,6 +39,10 @@ def adversarial_rows(V, rng, bf16):
     blk = 0.1 * rng.standard_normal(V); blk[:: 8 * 256] += 10.0           # maxima land in one lane's chunks
     add("strided_maxima", blk)
     add("signed_zeros", np.where(rng.random(V) < 0.5, -0.0, 0.0))
+    zh = np.where(rng.random(V) < 0.5, -0.0, 0.0); zh[rng.choice(V, min(V, 48), replace=False)] = rng.uniform(1, 9, min(V, 48))
+    add("zeros_with_positive_head", zh)                                  # below-window values inside the fast path
+    tn = 3 * rng.standard_normal(V); tn[rng.random(V) < 0.01] = 1e-9; tn[rng.random(V) < 0.01] = -1e-12
+    add("sprinkled_tiny", tn)
     lowhigh = -20 + rng.standard_normal(V); lowhigh[V // 2:] += 60       # reference must be raised mid-row
     add("late_large", lowhigh)
     return names, np.stack(rows)

@@ -249,7 +249,7 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
   }
   const int FK = c.max_frontier * c.top_k;
   const int nt = FK <= 256 ? 256 : 1024;
-  const size_t lds = (size_t)(((5 * c.hidden + 1 + 3) & ~3) + 4 * FK) * 4;
+  const size_t lds = (size_t)(((5 * c.hidden + 1 + 3) & ~3) + 5 * ((FK + 3) & ~3)) * 4;
   hipLaunchKernelGGL(k_score_prune, dim3(c.batch), dim3(nt), lds, s, x->st, x->part, x->part_topv, x->part_topi,
                      nsplit, rows_per_seq, c.max_frontier, c.top_k, c.budget, c.hidden, x->layer, x->z_beta);
   if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;

@@ -36,30 +36,72 @@ __device__ __forceinline__ int lane_id() {
   return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
+// ---- wavefront reductions and scan on DPP (data-parallel primitives: lane permutations inside
+// the VALU, no LDS round trip).  Rows are groups of 16 lanes.  The combination order is fixed, so
+// floating-point results are reproducible.
+#define C2T_DPP_QUAD_XOR1 0xB1      /* quad_perm [1,0,3,2] */
+#define C2T_DPP_QUAD_XOR2 0x4E      /* quad_perm [2,3,0,1] */
+#define C2T_DPP_ROW_HALF_MIRROR 0x141
+#define C2T_DPP_ROW_MIRROR 0x140
+#define C2T_DPP_ROW_BCAST15 0x142
+#define C2T_DPP_ROW_BCAST31 0x143
+#define C2T_DPP_ROW_SHR(n) (0x110 | (n))
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+  return __uint_as_float(dpp_u32<CTRL, ROW_MASK>(__float_as_uint(identity), __float_as_uint(v)));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {      // identity 0.0
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t lo = dpp_u32<CTRL, ROW_MASK>(0u, (uint32_t)u), hi = dpp_u32<CTRL, ROW_MASK>(0u, (uint32_t)(u >> 32));
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ uint32_t readlane63_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, 63); }
+
+// every lane of a row gets the row's result; then lane 63 gets the wave's (read it with readlane63)
+template <typename Op>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t v, uint32_t ident, Op op) {
+  v = op(v, dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(ident, v));
+  v = op(v, dpp_u32<C2T_DPP_QUAD_XOR2, 0xf>(ident, v));
+  v = op(v, dpp_u32<C2T_DPP_ROW_HALF_MIRROR, 0xf>(ident, v));
+  v = op(v, dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(ident, v));
+  v = op(v, dpp_u32<C2T_DPP_ROW_BCAST15, 0xa>(ident, v));
+  v = op(v, dpp_u32<C2T_DPP_ROW_BCAST31, 0xc>(ident, v));
+  return readlane63_u32(v);
+}
+__device__ __forceinline__ float wave_max(float v) {
+  return __uint_as_float(wave_reduce_u32(__float_as_uint(v), __float_as_uint(-INFINITY),
+                                         [](uint32_t a, uint32_t b) { return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b))); }));
 }
 __device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+  return (int)wave_reduce_u32((uint32_t)v, 0u, [](uint32_t a, uint32_t b) { return a + b; });
 }
-// inclusive prefix sum across the wave
+__device__ __forceinline__ double wave_sum(double v) {
+  v = v + dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(v);
+  v = v + dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(v);
+  v = v + dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(v);
+  v = v + dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(v);
+  v = v + dpp_f64<C2T_DPP_ROW_BCAST15, 0xa>(v);
+  v = v + dpp_f64<C2T_DPP_ROW_BCAST31, 0xc>(v);
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t lo = readlane63_u32((uint32_t)u), hi = readlane63_u32((uint32_t)(u >> 32));
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+// inclusive prefix sum across the wave (Hillis-Steele inside each row, then row carries)
 __device__ __forceinline__ int wave_scan_incl(int v) {
-  const int l = lane_id();
-#pragma unroll
-  for (int o = 1; o < WAVE; o <<= 1) {
-    int t = __shfl_up(v, o, WAVE);
-    if (l >= o) v += t;
-  }
-  return v;
+  uint32_t u = (uint32_t)v;
+  u += dpp_u32<C2T_DPP_ROW_SHR(1), 0xf>(0u, u);
+  u += dpp_u32<C2T_DPP_ROW_SHR(2), 0xf>(0u, u);
+  u += dpp_u32<C2T_DPP_ROW_SHR(4), 0xf>(0u, u);
+  u += dpp_u32<C2T_DPP_ROW_SHR(8), 0xf>(0u, u);
+  u += dpp_u32<C2T_DPP_ROW_BCAST15, 0xa>(0u, u);
+  u += dpp_u32<C2T_DPP_ROW_BCAST31, 0xc>(0u, u);
+  return (int)u;
 }
 
 // K-th largest (k >= 1) of the keys held by one wave, NV keys per lane (invalid keys = 0,

@@ -152,7 +152,7 @@ __device__ __forceinline__ int finish_topk(const uint4* __restrict__ rowp, int c
   for (int e = tid; e < n_el; e += NT) {
     const float v = el_v[e]; const int id = el_i[e];
     int rank = 0;
-#pragma unroll 2
+#pragma unroll 4
     for (int o = 0; o < n_el; ++o) {
       const float vo = el_v[o];
       rank += (vo > v) || (vo == v && el_i[o] < id);
@@ -502,12 +502,8 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   // per-wave: magnitude range and maximum
   {
     uint32_t mx = a.mag_max;
-    float mw = a.M;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      mx = pk_max_u16(mx, __shfl_xor(mx, o, WAVE));
-      mw = fmaxf(mw, __shfl_xor(mw, o, WAVE));
-    }
+    mx = wave_reduce_u32(mx, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
+    const float mw = wave_max(a.M);
     if (lane == 0) { red_u[wid] = mx; red_f[wid] = mw; }
   }
   __syncthreads();                                     // histogram, cell map and wave results complete
@@ -519,8 +515,8 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   double Z = 0.0, S = 0.0;
   int lane_total = 0;
   float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
+  uint32_t n[HP_BPL];
   {
-    uint32_t n[HP_BPL];
 #pragma unroll
     for (int j = 0; j < HP_BPL; ++j) {
       n[j] = hist[hp_bin_of_code(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)))];
@@ -552,16 +548,24 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   for (int w = 0; w < HP_NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m = fmaxf(m, red_f[w]); }
   const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16);
   const int n_tiny = sh_ntiny;
-  if (tid == 0) {                                       // fixed order: waves ascending
+  if (wid == 0) {                                       // lanes 0..15 hold one wave's sums each; fixed order
     double tz = 0.0, ts = 0.0;
-#pragma unroll 1
-    for (int w = 0; w < HP_NW; ++w)
-      if (red_d[0][w] > 0.0) { tz += red_d[0][w]; ts += red_d[1][w] + ((double)red_v[w] - (double)m) * red_d[0][w]; }
-    if (n_tiny) {                                       // e^x = 1 + x, x e^x = x for |x| < 2^-25
-      const double zt = (double)n_tiny + sh_stiny;
-      tz += zt; ts += sh_stiny - (double)m * zt;
+    if (lane < HP_NW && red_d[0][lane] > 0.0) {
+      tz = red_d[0][lane];
+      ts = red_d[1][lane] + ((double)red_v[lane] - (double)m) * tz;
     }
-    sum_d[0] = tz; sum_d[1] = ts;
+    static_assert(HP_NW == 16, "one DPP row holds the per-wave partials");
+    tz += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(ts);
+    tz += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(ts);
+    tz += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(ts);
+    tz += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(ts);
+    if (lane == 0) {
+      if (n_tiny) {                                     // e^x = 1 + x, x e^x = x for |x| < 2^-25
+        const double zt = (double)n_tiny + sh_stiny;
+        tz += zt; ts += sh_stiny - (double)m * zt;
+      }
+      sum_d[0] = tz; sum_d[1] = ts;
+    }
   }
   // tau = exact K-th largest logit: first rank (from the top) where the running count reaches K
   {
@@ -570,12 +574,10 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
     for (int w = 0; w < HP_NW; ++w) if (w < wid) above += scan_tmp[0][w];
     if (above < K && above + lane_total >= K) {          // exactly one lane
       int run = above;
-#pragma unroll 1
+#pragma unroll
       for (int j = 0; j < HP_BPL; ++j) {
-        const int r = HP_BINS - 1 - (tid * HP_BPL + j);
-        const int n = (int)hist[hp_bin_of_code(hp_code_of_rank(r))];
-        if (run < K && run + n >= K) { sh_tau_rank = r; sh_n_gt = run; }
-        run += n;
+        if (run < K && run + (int)n[j] >= K) { sh_tau_rank = HP_BINS - 1 - (tid * HP_BPL + j); sh_n_gt = run; }
+        run += (int)n[j];
       }
     }
   }

@@ -45,6 +45,7 @@ __global__ void k_reset(TreeState s, int B, int F, int D) {
 __device__ __forceinline__ float mlp_logit(const float* __restrict__ w, int h, float P, float H, float d) {
   const float* W1 = w; const float* b1 = w + 3 * h; const float* w2 = w + 4 * h;
   float z = w[5 * h];
+#pragma unroll 4
   for (int j = 0; j < h; ++j) {
     float a = __fmaf_rn(W1[3 * j + 0], P, b1[j]);
     a = __fmaf_rn(W1[3 * j + 1], H, a);
@@ -57,18 +58,20 @@ __device__ __forceinline__ float mlp_logit(const float* __restrict__ w, int h, f
 
 constexpr int SP_MAX_F = 64;
 
-// One workgroup per sequence.  Dynamic LDS: (5h+1) floats + F*K * (float z, int tok, int surv, float P).
+// One workgroup per sequence.  Dynamic LDS: (5h+1) floats (padded to 4) + 5 arrays of F*K (padded to 4)
+// 4-byte entries: z, token, survivor index, P, survivor z.
 __global__ __launch_bounds__(1024) void k_score_prune(
     TreeState s, const RowPartial* __restrict__ part, const float* __restrict__ part_topv,
     const int32_t* __restrict__ part_topi, int nsplit, int rows_per_seq, int F, int K, int N, int h, int layer,
     float z_beta) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   float* w = (float*)dyn_lds;
-  const int FK = F * K;
+  const int FK = F * K, FKp = (FK + 3) & ~3;
   float* cz = w + ((5 * h + 1 + 3) & ~3);
-  int32_t* ctok = (int32_t*)(cz + FK);
-  int32_t* surv = ctok + FK;
-  float* cP = (float*)(surv + FK);
+  int32_t* ctok = (int32_t*)(cz + FKp);
+  int32_t* surv = ctok + FKp;
+  float* cP = (float*)(surv + FKp);
+  float* sz = cP + FKp;                                   // z of the survivors, contiguous, 16-byte aligned
   __shared__ double rowZ[SP_MAX_F], rowC[SP_MAX_F];
   __shared__ float rowH[SP_MAX_F], parP[SP_MAX_F];
   __shared__ int32_t rowBad[SP_MAX_F], parNode[SP_MAX_F];
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(1024) void k_score_prune(
     const int64_t o = (int64_t)b * FK + i;
     s.c_tok[o] = tok; s.c_p[o] = p32; s.c_P[o] = P32; s.c_H[o] = rowBad[f] ? 0.f : rowH[f]; s.c_z[o] = z;
     s.c_kept[o] = 0;
-    if (tok >= 0 && z > z_beta) surv[atomicAdd(&n_surv, 1)] = i;
+    if (tok >= 0 && z > z_beta) { const int u = atomicAdd(&n_surv, 1); surv[u] = i; sz[u] = z; }
   }
   __syncthreads();
 
@@ -196,17 +199,26 @@ __global__ __launch_bounds__(1024) void k_score_prune(
   __shared__ float new_P[SP_MAX_F];
   for (int u = tid; u < ns; u += nt) {
     const int i = surv[u];
-    const float z = cz[i]; const int tok = ctok[i];
+    const float z = sz[u]; const int tok = ctok[i];
     int rank = 0;
-    for (int v = 0; v < ns; ++v) {
+    // survivors ahead of this one: larger z, or equal z and (token, slot) smaller
+    auto tie = [&](int v) {
       const int j = surv[v];
-      const float zj = cz[j];
-      if (zj > z) ++rank;
-      else if (zj == z && j != i) {
-        const int tj = ctok[j];
-        rank += (tj < tok) || (tj == tok && j < i);      // same token: lower slot (= lower index) first
+      if (j != i) { const int tj = ctok[j]; rank += (tj < tok) || (tj == tok && j < i); }
+    };
+    int v = 0;
+#pragma unroll 2
+    for (; v + 4 <= ns; v += 4) {
+      const float4 q = *(const float4*)(sz + v);
+      rank += (q.x > z) + (q.y > z) + (q.z > z) + (q.w > z);
+      if (q.x == z || q.y == z || q.z == z || q.w == z) {
+        if (q.x == z) tie(v);
+        if (q.y == z) tie(v + 1);
+        if (q.z == z) tie(v + 2);
+        if (q.w == z) tie(v + 3);
       }
     }
+    for (; v < ns; ++v) { const float zj = sz[v]; if (zj > z) ++rank; else if (zj == z) tie(v); }
     if (rank < n_keep) {
       const int f = i / K;
       const int node = nn + rank;

@@ -20,9 +20,11 @@ using namespace c2t;
 namespace {
 
 constexpr size_t ALIGN = 256;
-// Cell map of one workgroup.  bf16: the histogram kernel holds 40 KB of static LDS, and two
-// workgroups of 1024 threads must fit the CU's 160 KB, so its map gets at most 40 KB.
-constexpr int MAX_MAP_BYTES_BF16 = 40 * 1024;
+static_assert(C2T_MAX_CANDIDATES == C2T_MAX_CANDIDATES_DEV && C2T_MAX_FRONTIER == SP_MAX_F && C2T_MAX_TOP_K == 64,
+              "limits of the C ABI and of the kernels must agree");
+// Cell map of one workgroup.  bf16: two workgroups of 1024 threads must fit the CU's 160 KB, each with
+// the 32 KB histogram, 10.1 KB of static LDS and the map: 80 KB - 32 KB - 10336 B = 38816 B at most.
+constexpr int MAX_MAP_BYTES_BF16 = 38528;
 constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
 constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
 constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
@@ -31,7 +33,7 @@ constexpr int TARGET_WORKGROUPS = 512;         // two workgroups per CU; beyond 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
-  size_t cls, n_nodes, n_frontier, status, n_cand, layer_rows;
+  size_t cls, n_nodes, nf0, nf1, tickets, row_tickets, row_info, status, n_cand, layer_rows;
   size_t fr_tok, fr_pslot, fr_node, fr_P;
   size_t t_tok, t_parent, t_depth, t_P, t_H, t_z;
   size_t c_tok, c_p, c_P, c_H, c_z, c_kept;
@@ -71,7 +73,8 @@ Layout make_layout(const c2t_config& c) {
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   const size_t B = c.batch, F = c.max_frontier, K = c.top_k, N = c.budget, h = c.hidden;
   L.cls = take((5 * h + 1) * 4);
-  L.n_nodes = take(B * 4); L.n_frontier = take(B * 4); L.status = take(B * 4); L.n_cand = take(B * 4);
+  L.n_nodes = take(B * 4); L.nf0 = take(B * 4); L.nf1 = take(B * 4); L.tickets = take(B * 4);
+  L.row_tickets = take(B * F * 4); L.row_info = take(B * F * 4); L.status = take(B * 4); L.n_cand = take(B * 4);
   L.layer_rows = take((c.max_depth + 1) * 4);
   L.fr_tok = take(B * F * 4); L.fr_pslot = take(B * F * 4); L.fr_node = take(B * F * 4); L.fr_P = take(B * F * 4);
   L.t_tok = take(B * N * 4); L.t_parent = take(B * N * 4); L.t_depth = take(B * N * 4);
@@ -124,23 +127,32 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
                          hipStream_t s) {
   const c2t_config& c = x->cfg;
   const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
-  const size_t lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)SEL_ELEM_CAP * 8);
+  const size_t map_lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)SEL_ELEM_CAP * 8);
+  const size_t score_lds = score_lds_bytes(c.hidden, c.max_frontier * c.top_k);
   const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
+  ScoreParams sp;
+  sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
+  sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
+  sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta;
   if (c.logits_dtype == C2T_BF16) {
     static bool lds_raised = false;       // static + dynamic LDS of this kernel exceeds the 64 KB default
     if (!lds_raised) {
       hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         MAX_MAP_BYTES_BF16);
+                                         HP_BINS * 4 + MAX_MAP_BYTES_BF16);
       if (e != hipSuccess) return e;
       lds_raised = true;
     }
-    hipLaunchKernelGGL(k_logits_hist, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, c.top_k,
-                       c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->tab_e, x->part,
-                       x->part_topv, x->part_topi);
+    const size_t lds = std::max<size_t>((size_t)HP_BINS * 4 + map_lds, score_lds);
+    sp.lds_bytes = (int)lds;
+    const char* sv = getenv("C2T_STAGGER_US");
+    const int stagger_ticks = sv ? atoi(sv) * 100 : 0;
+    hipLaunchKernelGGL(k_logits_hist, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
+                       x->st, sp, stagger_ticks > 0 ? 512 : 0, stagger_ticks);
   } else {
+    const size_t lds = std::max<size_t>(map_lds, score_lds);
+    sp.lds_bytes = (int)lds;
     hipLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, logits, stride, c.vocab,
-                       c.top_k, c.max_frontier, rows_per_seq, x->st.n_frontier, nsplit, cps, x->part, x->part_topv,
-                       x->part_topi);
+                       cps, x->st, sp);
   }
   return hipGetLastError();
 }
@@ -170,7 +182,9 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   char* w = x->ws;
   TreeState& s = x->st;
   s.cls = (float*)(w + L.cls);
-  s.n_nodes = (int32_t*)(w + L.n_nodes); s.n_frontier = (int32_t*)(w + L.n_frontier);
+  s.n_nodes = (int32_t*)(w + L.n_nodes); s.nf[0] = (int32_t*)(w + L.nf0); s.nf[1] = (int32_t*)(w + L.nf1);
+  s.tickets = (int32_t*)(w + L.tickets); s.row_tickets = (int32_t*)(w + L.row_tickets);
+  s.row_info = (uint32_t*)(w + L.row_info);
   s.status = (uint32_t*)(w + L.status); s.n_cand = (int32_t*)(w + L.n_cand);
   s.layer_rows = (int32_t*)(w + L.layer_rows);
   s.fr_tok = (int32_t*)(w + L.fr_tok); s.fr_pslot = (int32_t*)(w + L.fr_pslot);
@@ -247,12 +261,6 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
     if (hipEventRecord(x->ev[x->ev_used + 1], s) != hipSuccess) return C2T_ERR_HIP;
     x->ev_used += 2;
   }
-  const int FK = c.max_frontier * c.top_k;
-  const int nt = FK <= 256 ? 256 : 1024;
-  const size_t lds = (size_t)(((5 * c.hidden + 1 + 3) & ~3) + 5 * ((FK + 3) & ~3)) * 4;
-  hipLaunchKernelGGL(k_score_prune, dim3(c.batch), dim3(nt), lds, s, x->st, x->part, x->part_topv, x->part_topi,
-                     nsplit, rows_per_seq, c.max_frontier, c.top_k, c.budget, c.hidden, x->layer, x->z_beta);
-  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
   x->layer += 1;
   return C2T_OK;
 }
@@ -261,7 +269,7 @@ int c2t_get_frontier(c2t_ctx* x, const int32_t** tokens, const int32_t** parent_
   if (!x) return C2T_ERR_INVALID_ARG;
   if (tokens) *tokens = x->st.fr_tok;
   if (parent_slot) *parent_slot = x->st.fr_pslot;
-  if (n_frontier) *n_frontier = x->st.n_frontier;
+  if (n_frontier) *n_frontier = x->st.nf[(x->layer < 0 ? 0 : x->layer) & 1];
   return C2T_OK;
 }
 

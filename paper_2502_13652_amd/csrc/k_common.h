@@ -19,6 +19,33 @@ struct __attribute__((aligned(16))) RowPartial {
   uint32_t flags; // bit 0: NaN or +inf seen; bit 1 (informational): a bf16 segment took the two-pass path
 };
 
+// Device-coherent accesses for data one workgroup writes and another reads inside the same kernel:
+// they go to the coherence point, so neither side needs cache-wide write-backs or invalidations.
+__device__ __forceinline__ void st_dev(uint32_t* p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(int32_t* p, int32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(float* p, float v) { st_dev((uint32_t*)p, __float_as_uint(v)); }
+__device__ __forceinline__ void st_dev(double* p, double v) {
+  __hip_atomic_store((unsigned long long*)p, (unsigned long long)__double_as_longlong(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_dev(const int32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t ld_dev(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float* p) { return __uint_as_float(ld_dev((const uint32_t*)p)); }
+__device__ __forceinline__ double ld_dev(const double* p) {
+  return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void st_dev(RowPartial* p, const RowPartial& r) {
+  st_dev(&p->ref, r.ref); st_dev(&p->a, r.a); st_dev(&p->Z, r.Z); st_dev(&p->S, r.S);
+  st_dev(&p->n_top, r.n_top); st_dev(&p->flags, r.flags);
+}
+__device__ __forceinline__ RowPartial ld_dev(const RowPartial* p) {
+  RowPartial r;
+  r.ref = ld_dev(&p->ref); r.a = ld_dev(&p->a); r.Z = ld_dev(&p->Z); r.S = ld_dev(&p->S);
+  r.n_top = ld_dev(&p->n_top); r.flags = ld_dev(&p->flags);
+  return r;
+}
+// every vector memory operation this wave has issued is complete
+__device__ __forceinline__ void wait_vector_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 

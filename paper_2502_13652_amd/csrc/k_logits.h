@@ -26,6 +26,7 @@
 // and their elements ranked exactly by (logit desc, id asc).
 #pragma once
 #include "k_common.h"
+#include "k_tree.h"
 
 namespace c2t {
 
@@ -124,7 +125,7 @@ __device__ __forceinline__ bool build_cell_list(const typename LogitTraits<DT>::
 template <int DT, int NT>
 __device__ __forceinline__ int finish_topk(const uint4* __restrict__ rowp, int c0, int V, int K, float tau,
                                            const int32_t* cell_list, int n_cells, unsigned char* dyn_lds,
-                                           int32_t* sh_cnt, float* __restrict__ topv, int32_t* __restrict__ topi) {
+                                           int32_t* sh_cnt, float* topv, int32_t* topi) {
   typedef LogitTraits<DT> T;
   const int tid = threadIdx.x;
   float* el_v = (float*)dyn_lds;
@@ -202,8 +203,7 @@ __device__ __forceinline__ float block_max(float v, float* red /*[NT/WAVE]*/) {
 // ---------------------------------------------------------------------------------------
 template <int DT, int NT>
 __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, const Segment sg,
-                                unsigned char* dyn_lds, RowPartial* __restrict__ part_out,
-                                float* __restrict__ topv, int32_t* __restrict__ topi, uint32_t info_flags) {
+                                unsigned char* dyn_lds, RowResult* rr, uint32_t info_flags) {
   typedef LogitTraits<DT> T;
   typedef typename T::key_t key_t;
   constexpr int NW = NT / WAVE;
@@ -299,32 +299,39 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
     tau = prefix ? key_to_float(prefix) : -INFINITY;
     build_cell_list<DT, NT>(map, sg.ncell, tau, K, cell_list, scan_tmp, &n_cells);   // now <= 2K-1 cells
   }
-  const int n_top = finish_topk<DT, NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt, topv, topi);
+  const int n_top = finish_topk<DT, NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt, rr->topv, rr->topi);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = (double)m; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = seg_bad ? 0 : n_top; r.flags = (seg_bad ? 1u : 0u) | info_flags;
-    *part_out = r;
+    rr->part = r;
   }
 }
 
+// Workgroups of a sequence whose frontier is empty have nothing to read; the first of them
+// records the empty next frontier (Algorithm 1's loop guard) in place of the scoring step.
+__device__ __forceinline__ void end_of_sequence(const TreeState& st, const ScoreParams& sp, int b, int f, int split) {
+  if (f == 0 && split == 0 && threadIdx.x == 0) { st.nf[(sp.layer + 1) & 1][b] = 0; st.n_cand[b] = 0; }
+}
+
 // grid: rows_launched * nsplit workgroups of NT threads.
-// Dynamic LDS: max(cps * sizeof(key_t), SEL_ELEM_CAP * 8) bytes.
+// Dynamic LDS: max(cps * sizeof(key_t), SEL_ELEM_CAP * 8, score_lds_bytes) bytes.
 template <int DT, int NT>
 __global__ __launch_bounds__(NT) void k_logits_generic(
-    const void* __restrict__ logits, int64_t row_stride_elems, int V, int K, int F, int rows_per_seq,
-    const int32_t* __restrict__ n_frontier, int nsplit, int cps, RowPartial* __restrict__ part,
-    float* __restrict__ part_topv, int32_t* __restrict__ part_topi) {
+    const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, TreeState st, ScoreParams sp) {
   typedef LogitTraits<DT> T;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
+  const int nsplit = sp.nsplit, K = sp.K;
   const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
-  const int b = rl / rows_per_seq, f = rl % rows_per_seq;
-  if (f >= n_frontier[b]) return;                       // uniform for the workgroup
-  const int64_t row = (int64_t)b * F + f;
+  const int b = rl / sp.rows_per_seq, f = rl % sp.rows_per_seq;
+  const int nf = st.nf[sp.layer & 1][b];
+  if (f >= nf) { if (nf == 0) end_of_sequence(st, sp, b, f, split); return; }   // uniform for the workgroup
+  const int64_t row = (int64_t)b * sp.F + f;
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * (DT == 1 ? 2 : 4));
   const Segment sg = make_segment<T::EPC>(V, split, cps);
-  const int64_t po = (int64_t)rl * nsplit + split;      // partial records are indexed by launched row
-  if (sg.ncell == 0) { if (threadIdx.x == 0) part[po] = empty_partial(); return; }
-  generic_segment<DT, NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 0u);
+  __shared__ RowResult rr;
+  if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
+  else generic_segment<DT, NT>(rowp, V, K, sg, dyn_lds, &rr, 0u);
+  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds);         // split records are indexed by launched row
 }
 
 // ---------------------------------------------------------------------------------------
@@ -428,15 +435,12 @@ __device__ __forceinline__ void hist_chunk(const uint4& q, HistLane& a, uint32_t
   }
 }
 
-// grid: rows_launched * nsplit workgroups of HP_NT threads.
-// Dynamic LDS: max(cps * 2, SEL_ELEM_CAP * 8) bytes (cell map / element list).
-__global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
-    const void* __restrict__ logits, int64_t row_stride_elems, int V, int K, int F, int rows_per_seq,
-    const int32_t* __restrict__ n_frontier, int nsplit, int cps, const double* __restrict__ tab_e,
-    RowPartial* __restrict__ part, float* __restrict__ part_topv, int32_t* __restrict__ part_topi) {
-  extern __shared__ __align__(16) unsigned char dyn_lds[];
-  uint16_t* map = (uint16_t*)dyn_lds;
-  __shared__ uint32_t hist[HP_BINS];
+// One (row, split) segment on the histogram path, run by a whole workgroup of HP_NT threads.
+// hist: HP_BINS counters, map_lds: max(cps * 2, SEL_ELEM_CAP * 8) bytes (cell map / element list).
+__device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, const Segment& sg,
+                                             const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
+                                             unsigned char* map_lds, RowResult* rr) {
+  uint16_t* map = (uint16_t*)map_lds;
   __shared__ double red_d[2][HP_NW], sum_d[2];
   __shared__ float red_f[HP_NW], red_v[HP_NW];
   __shared__ uint32_t red_u[HP_NW];
@@ -447,14 +451,6 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   __shared__ int32_t sh_cnt, sh_ncell, sh_tau_rank, sh_n_gt;
 
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
-  const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
-  const int b = rl / rows_per_seq, f = rl % rows_per_seq;
-  if (f >= n_frontier[b]) return;                       // uniform for the workgroup
-  const int64_t row = (int64_t)b * F + f;
-  const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
-  const Segment sg = make_segment<8>(V, split, cps);
-  const int64_t po = (int64_t)rl * nsplit + split;
-  if (sg.ncell == 0) { if (tid == 0) part[po] = empty_partial(); return; }
 
 #pragma unroll
   for (int j = 0; j < HP_BPL; ++j) hist[tid + j * HP_NT] = 0u;
@@ -587,7 +583,7 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   // could be among the top K, which the histogram cannot rank).
   if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || (n_tiny > 0 && sh_tau_rank < HP_BINS / 2)) {
     __syncthreads();
-    generic_segment<1, HP_NT>(rowp, V, K, sg, dyn_lds, part + po, part_topv + po * K, part_topi + po * K, 2u);
+    generic_segment<1, HP_NT>(rowp, V, K, sg, map_lds, rr, 2u);
     return;
   }
   float tau = -INFINITY;
@@ -611,13 +607,43 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   int n_cells = sh_ncell;
   if (n_cells > SEL_CELL_CAP)                            // massive ties at tau
     build_cell_list<1, HP_NT>(map, sg.ncell, tau, eq_limit, cell_list, scan_tmp, &n_cells);
-  const int n_top = finish_topk<1, HP_NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt,
-                                          part_topv + po * K, part_topi + po * K);
+  const int n_top = finish_topk<1, HP_NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, map_lds, &sh_cnt, rr->topv, rr->topi);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
-    part[po] = r;
+    rr->part = r;
   }
+}
+
+// grid: rows_launched * nsplit workgroups of HP_NT threads.
+// Dynamic LDS: [HP_BINS counters | max(cps * 2, SEL_ELEM_CAP * 8) bytes of cell map / element list];
+// the scoring step of the sequence's last workgroup reuses all of it.
+__global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
+    const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
+    TreeState st, ScoreParams sp, int stagger_wgs, int stagger_ticks) {
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  const int nsplit = sp.nsplit, K = sp.K;
+  // Two workgroups share a compute unit.  Started together they stream together and then run their
+  // epilogues together, leaving the memory system idle; delaying the second one of the first round
+  // makes the pairs alternate (later workgroups inherit the phase of the one they replace).
+  if ((int)blockIdx.x < stagger_wgs) {
+    const uint32_t lds_base = __builtin_amdgcn_s_getreg((7 << 11) | (0 << 6) | 6);   // HW_REG_LDS_ALLOC, LDS_BASE
+    if (lds_base != 0) {
+      const uint64_t t0 = wall_clock64();
+      for (int spin = 0; spin < 64 && (int64_t)(wall_clock64() - t0) < stagger_ticks; ++spin) __builtin_amdgcn_s_sleep(64);
+    }
+  }
+  const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
+  const int b = rl / sp.rows_per_seq, f = rl % sp.rows_per_seq;
+  const int nf = st.nf[sp.layer & 1][b];
+  if (f >= nf) { if (nf == 0) end_of_sequence(st, sp, b, f, split); return; }   // uniform for the workgroup
+  const int64_t row = (int64_t)b * sp.F + f;
+  const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
+  const Segment sg = make_segment<8>(V, split, cps);
+  __shared__ RowResult rr;
+  if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
+  else hist_segment(rowp, V, K, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_BINS * 4, &rr);
+  finish_layer<HP_NT>(st, sp, b, f, split, rl, rr, dyn_lds);
 }
 
 // Plain streaming read: the practical HBM ceiling.

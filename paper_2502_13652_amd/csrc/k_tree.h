@@ -9,7 +9,10 @@ namespace c2t {
 struct TreeState {            // device pointers into the workspace
   float* cls;                 // W1[3h] b1[h] w2[h] b2
   int32_t* n_nodes;           // [B]
-  int32_t* n_frontier;        // [B]
+  int32_t* nf[2];             // [B] frontier sizes, ping-pong: layer l reads nf[l&1], writes nf[(l+1)&1]
+  int32_t* tickets;           // [B] rows of the current layer that have been scored
+  int32_t* row_tickets;       // [B][F] splits of the row that have delivered their record
+  uint32_t* row_info;         // [B][F] bit 0: row unusable (NaN, +inf, no finite logit); bit 1: two-pass path taken
   uint32_t* status;           // [B]
   int32_t* n_cand;            // [B]
   int32_t* layer_rows;        // [D+1]
@@ -34,11 +37,12 @@ struct TreeState {            // device pointers into the workspace
 __global__ void k_reset(TreeState s, int B, int F, int D) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B) {
-    s.n_nodes[i] = 0; s.n_frontier[i] = 1; s.status[i] = 0; s.n_cand[i] = 0;
+    s.n_nodes[i] = 0; s.nf[0][i] = 1; s.nf[1][i] = 0; s.tickets[i] = 0; s.status[i] = 0; s.n_cand[i] = 0;
     s.fr_tok[(int64_t)i * F] = -1; s.fr_pslot[(int64_t)i * F] = 0;
     s.fr_node[(int64_t)i * F] = -1; s.fr_P[(int64_t)i * F] = 1.0f;
   }
   if (i <= D) s.layer_rows[i] = (i == 0) ? B : 0;
+  for (int j = i; j < B * F; j += gridDim.x * blockDim.x) s.row_tickets[j] = 0;
 }
 
 // Eq. 3 in fp32: fixed chain of fused multiply-adds, hidden units in ascending order.
@@ -57,176 +61,234 @@ __device__ __forceinline__ float mlp_logit(const float* __restrict__ w, int h, f
 }
 
 constexpr int SP_MAX_F = 64;
+constexpr int C2T_MAX_CANDIDATES_DEV = 2048;              // F*K limit of the per-sequence step
 
-// One workgroup per sequence.  Dynamic LDS: (5h+1) floats (padded to 4) + 5 arrays of F*K (padded to 4)
-// 4-byte entries: z, token, survivor index, P, survivor z.
-__global__ __launch_bounds__(1024) void k_score_prune(
-    TreeState s, const RowPartial* __restrict__ part, const float* __restrict__ part_topv,
-    const int32_t* __restrict__ part_topi, int nsplit, int rows_per_seq, int F, int K, int N, int h, int layer,
-    float z_beta) {
-  extern __shared__ __align__(16) unsigned char dyn_lds[];
-  float* w = (float*)dyn_lds;
-  const int FK = F * K, FKp = (FK + 3) & ~3;
-  float* cz = w + ((5 * h + 1 + 3) & ~3);
-  int32_t* ctok = (int32_t*)(cz + FKp);
-  int32_t* surv = ctok + FKp;
-  float* cP = (float*)(surv + FKp);
-  float* sz = cP + FKp;                                   // z of the survivors, contiguous, 16-byte aligned
-  __shared__ double rowZ[SP_MAX_F], rowC[SP_MAX_F];
-  __shared__ float rowH[SP_MAX_F], parP[SP_MAX_F];
-  __shared__ int32_t rowBad[SP_MAX_F], parNode[SP_MAX_F];
-  __shared__ int32_t n_surv, any_bad, any_slow;
+struct ScoreParams {
+  RowPartial* part; float* part_topv; int32_t* part_topi;    // [launched row][split] records and their top-K lists
+  int nsplit, rows_per_seq, F, K, N, h, layer;
+  int lds_bytes;                                             // dynamic LDS of the launch
+  float z_beta;
+};
 
-  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-  const int nf = s.n_frontier[b];
-  const int nn = s.n_nodes[b];
-  for (int i = tid; i < 5 * h + 1; i += nt) w[i] = s.cls[i];
-  if (tid == 0) { n_surv = 0; any_bad = 0; any_slow = 0; }
-  __syncthreads();
+// What one workgroup of the logits pass leaves in LDS for its (row, split): the record and the
+// segment's top-K list (value desc, id asc).
+struct RowResult {
+  RowPartial part;
+  float topv[64];
+  int32_t topi[64];
+};
 
-  // ---- per row: merge the splits (fp64), entropy of Eq. 2 ----
-  if (tid < nf) {
-    const RowPartial* rp = part + ((int64_t)b * rows_per_seq + tid) * nsplit;
+// LDS the tail needs: per sequence 3 arrays of F*K (padded to 4) 4-byte entries (token, survivor
+// index, survivor z padded to 32); per row the 5h+1 classifier weights; the row merge stages nsplit*K (value, id)
+// pairs when they fit.
+__host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
+  const size_t a = ((size_t)2 * ((FK + 3) & ~3) + ((FK + 31) & ~31)) * 4, b = (size_t)(5 * h + 1) * 4;
+  return a > b ? a : b;
+}
+
+// ---- row level, splits > 1: combine the row's split records (fp64) and top lists into `rr`.
+// Run by the workgroup that delivered the row's last split; `lds`/`lds_bytes` is free scratch.
+__device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_launched, RowResult& rr,
+                                          unsigned char* lds, size_t lds_bytes) {
+  const int tid = threadIdx.x, nt = blockDim.x, nsplit = sp.nsplit, K = sp.K;
+  const RowPartial* rp = sp.part + row_launched * nsplit;
+  const float* tv = sp.part_topv + row_launched * nsplit * K;
+  const int32_t* ti = sp.part_topi + row_launched * nsplit * K;
+  if (tid == 0) {
     double R = -INFINITY; uint32_t fl = 0;
-    for (int q = 0; q < nsplit; ++q) { R = fmax(R, rp[q].ref); fl |= rp[q].flags & 1u; if (rp[q].flags & 2u) any_slow = 1; }
+    for (int q = 0; q < nsplit; ++q) { R = fmax(R, ld_dev(&rp[q].ref)); fl |= ld_dev(&rp[q].flags); }
     double Z = 0.0, S = 0.0;
     for (int q = 0; q < nsplit; ++q) {
-      const double Zq = rp[q].Z;
-      if (Zq > 0.0 && rp[q].ref > -INFINITY) {
-        const double da = rp[q].a - R, dl = rp[q].ref - R;   // re-reference to the row maximum R; dl <= 0
+      const RowPartial pq = ld_dev(rp + q);
+      if (pq.Z > 0.0 && pq.ref > -INFINITY) {
+        const double da = pq.a - R, dl = pq.ref - R;         // re-reference to the row maximum R; dl <= 0
         const double sc = da == 0.0 ? 1.0 : exp(da);
-        Z += Zq * sc; S += (rp[q].S + dl * Zq) * sc;
+        Z += pq.Z * sc; S += (pq.S + dl * pq.Z) * sc;
       }
     }
-    const bool bad = fl != 0 || !(Z > 0.0) || !(R > -INFINITY) || !(R < INFINITY);
-    // p_j = e^(x_j - R) / Z  =>  H = -sum p ln p = ln Z - S / Z
-    const double H = bad ? 0.0 : log(Z) - S / Z;
-    rowZ[tid] = Z; rowC[tid] = R; rowH[tid] = (float)H; rowBad[tid] = bad;
-    parP[tid] = s.fr_P[(int64_t)b * F + tid];
-    parNode[tid] = s.fr_node[(int64_t)b * F + tid];
-    if (bad) any_bad = 1;
+    rr.part.ref = R; rr.part.a = R; rr.part.Z = Z; rr.part.S = S; rr.part.flags = fl; rr.part.n_top = 0;
   }
+  // An entry's merged rank = number of entries of the row's lists ahead of it.
+  const int per_row = nsplit * K;
+  float* sv = (float*)lds; int32_t* si = (int32_t*)(lds + (size_t)per_row * 4);
+  __shared__ int32_t n_valid;
+  if (tid == 0) n_valid = 0;
   __syncthreads();
-
-  // ---- merged top-K of each row: (logit, id) into (cz, ctok) ----
-  const int ncand = nf * K;
-  for (int i = tid; i < ncand; i += nt) { cz[i] = 0.f; ctok[i] = -1; }
-  __syncthreads();
-  if (nsplit == 1) {
-    for (int i = tid; i < ncand; i += nt) {
-      const int f = i / K, r = i % K;
-      const int64_t base = (int64_t)b * rows_per_seq + f;
-      if (!rowBad[f] && r < part[base].n_top) { cz[i] = part_topv[base * K + r]; ctok[i] = part_topi[base * K + r]; }
+  if ((size_t)per_row * 8 <= lds_bytes) {
+    for (int ent = tid; ent < per_row; ent += nt) {
+      const int q = ent / K, e = ent % K;
+      const bool ok = e < ld_dev(&rp[q].n_top);
+      sv[ent] = ok ? ld_dev(tv + ent) : 0.f;
+      si[ent] = ok ? ld_dev(ti + ent) : -1;
+      if (ok) atomicAdd(&n_valid, 1);
+    }
+    __syncthreads();
+    for (int ent = tid; ent < per_row; ent += nt) {
+      const int vi = si[ent];
+      if (vi < 0) continue;
+      const float v = sv[ent];
+      int ahead = 0;
+      for (int o = 0; o < per_row; ++o) {
+        const int oi = si[o];
+        ahead += oi >= 0 && ((sv[o] > v) || (sv[o] == v && oi < vi));
+      }
+      if (ahead < K) { rr.topv[ahead] = v; rr.topi[ahead] = vi; }
     }
   } else {
-    // An entry's merged rank = number of entries of the row's lists ahead of it.  Rows are taken
-    // in groups whose lists fit the staging area (surv/cP are free until the scoring step).
-    float* sv = (float*)surv; int32_t* si = (int32_t*)cP;
-    const int per_row = nsplit * K;
-    const int rows_per_group = max(1, FK / per_row);       // staging holds FK entries
-    for (int f0 = 0; f0 < nf; f0 += rows_per_group) {
-      const int nr = min(rows_per_group, nf - f0);
-      if (per_row <= FK) {
-        for (int ent = tid; ent < nr * per_row; ent += nt) {
-          const int f = f0 + ent / per_row, q = (ent % per_row) / K, e = ent % K;
-          const int64_t base = ((int64_t)b * rows_per_seq + f) * nsplit;
-          const bool ok = !rowBad[f] && e < part[base + q].n_top;
-          sv[ent] = ok ? part_topv[(base + q) * K + e] : 0.f;
-          si[ent] = ok ? part_topi[(base + q) * K + e] : -1;
-        }
-        __syncthreads();
-        for (int ent = tid; ent < nr * per_row; ent += nt) {
-          const int vi = si[ent];
-          if (vi < 0) continue;
-          const float v = sv[ent];
-          const int r0 = (ent / per_row) * per_row;
-          int ahead = 0;
-          for (int o = r0; o < r0 + per_row; ++o) {
-            const int oi = si[o];
-            ahead += oi >= 0 && ((sv[o] > v) || (sv[o] == v && oi < vi));
-          }
-          if (ahead < K) { const int f = f0 + ent / per_row; cz[f * K + ahead] = v; ctok[f * K + ahead] = vi; }
-        }
-        __syncthreads();
-      } else {
-        // one row's lists exceed the staging area (very many splits): rank from global memory
-        for (int ent = tid; ent < per_row; ent += nt) {
-          const int f = f0, q = ent / K, e = ent % K;
-          const int64_t base = ((int64_t)b * rows_per_seq + f) * nsplit;
-          if (rowBad[f] || e >= part[base + q].n_top) continue;
-          const float v = part_topv[(base + q) * K + e]; const int vi = part_topi[(base + q) * K + e];
-          int ahead = 0;
-          for (int q2 = 0; q2 < nsplit; ++q2) {
-            const int n2 = part[base + q2].n_top;
-            for (int e2 = 0; e2 < n2; ++e2) {
-              const float v2 = part_topv[(base + q2) * K + e2];
-              ahead += (v2 > v) || (v2 == v && part_topi[(base + q2) * K + e2] < vi);
-            }
-          }
-          if (ahead < K) { cz[f * K + ahead] = v; ctok[f * K + ahead] = vi; }
+    // the lists exceed the staging area (very many splits): rank from global memory
+    for (int ent = tid; ent < per_row; ent += nt) {
+      const int q = ent / K, e = ent % K;
+      if (e >= ld_dev(&rp[q].n_top)) continue;
+      atomicAdd(&n_valid, 1);
+      const float v = ld_dev(tv + ent); const int vi = ld_dev(ti + ent);
+      int ahead = 0;
+      for (int q2 = 0; q2 < nsplit; ++q2) {
+        const int n2 = ld_dev(&rp[q2].n_top);
+        for (int e2 = 0; e2 < n2; ++e2) {
+          const float v2 = ld_dev(tv + q2 * K + e2);
+          ahead += (v2 > v) || (v2 == v && ld_dev(ti + q2 * K + e2) < vi);
         }
       }
+      if (ahead < K) { rr.topv[ahead] = v; rr.topi[ahead] = vi; }
     }
   }
   __syncthreads();
+  if (tid == 0) rr.part.n_top = min(n_valid, K);
+  __syncthreads();
+}
 
-  // ---- per candidate: p, P (Eq. 1), z (Eq. 3), first pruning ----
-  for (int i = tid; i < ncand; i += nt) {
-    const int f = i / K;
-    float z = -INFINITY; int tok = -1;
-    float p32 = 0.f, P32 = 0.f;
-    {
-      const float x = cz[i]; const int id = ctok[i];
-      if (id >= 0) {
-        p32 = (float)(exp((double)x - rowC[f]) / rowZ[f]);
-        P32 = parP[f] * p32;
-        z = mlp_logit(w, h, P32, rowH[f], (float)layer);
-        tok = id;
-      }
+// ---- row level: entropy (Eq. 2), generation and joint probabilities (Eq. 1), classifier logit
+// (Eq. 3) of the row's K candidates, from the complete row result in `rr`.  One lane per candidate.
+__device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams& sp, int b, int f, const RowResult& rr,
+                                          float* w /* LDS, 5h+1 floats */) {
+  const int tid = threadIdx.x, K = sp.K;
+  const float parP = s.fr_P[(int64_t)b * sp.F + f];                          // requested together with the weights
+  for (int i = tid; i < 5 * sp.h + 1; i += blockDim.x) w[i] = s.cls[i];     // one coalesced read, then LDS broadcasts
+  __syncthreads();
+  if (tid >= K) return;
+  const double R = rr.part.ref, Z = rr.part.Z;
+  const uint32_t fl = rr.part.flags;
+  const bool bad = (fl & 1u) != 0 || !(Z > 0.0) || !(R > -INFINITY) || !(R < INFINITY);
+  // re-reference the sums from the offset a to the row maximum R (= ref): p_j = e^(x_j - R) / Zr,
+  // H = -sum p ln p = ln Zr - Sr / Zr
+  const double sc = rr.part.a == R ? 1.0 : exp(rr.part.a - R);
+  const double Zr = Z * sc, Sr = rr.part.S * sc;
+  const float H = bad ? 0.f : (float)(log(Zr) - Sr / Zr);
+  float z = -INFINITY, p32 = 0.f, P32 = 0.f; int tok = -1;
+  if (!bad && tid < rr.part.n_top) {
+    tok = rr.topi[tid];
+    p32 = (float)(exp((double)rr.topv[tid] - R) / Zr);
+    P32 = parP * p32;
+    z = mlp_logit(w, sp.h, P32, H, (float)sp.layer);
+  }
+  const int64_t o = (int64_t)b * sp.F * K + (int64_t)f * K + tid;
+  st_dev(s.c_tok + o, tok); st_dev(s.c_p + o, p32); st_dev(s.c_P + o, P32); st_dev(s.c_H + o, H); st_dev(s.c_z + o, z);
+  if (tid == 0) st_dev(s.row_info + (int64_t)b * sp.F + f, (uint32_t)(bad ? 1u : 0u) | (fl & 2u));
+}
+
+// ---- sequence level: both prunings of Sec. 4.2 with the node budget, tree append, next frontier.
+// Run by one whole workgroup once every row of the sequence has been scored.
+template <int NT>
+__device__ __forceinline__ void prune_sequence(const TreeState& s, const ScoreParams& sp, int b, unsigned char* lds) {
+  const int F = sp.F, K = sp.K, N = sp.N, layer = sp.layer;
+  const float z_beta = sp.z_beta;
+  const int FK = F * K, FKp = (FK + 3) & ~3;
+  int32_t* ctok = (int32_t*)lds;
+  int32_t* surv = ctok + FKp;
+  float* sz = (float*)(surv + FKp);                        // z of the survivors, contiguous, 16-byte aligned
+  __shared__ int32_t n_surv, flags_or;
+  __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
+  __shared__ float new_P[SP_MAX_F];
+
+  const int tid = threadIdx.x;
+  // T = 2^tshift consecutive lanes share a candidate and split the survivor list between them
+  // (T = 1 and several candidates per thread when F*K exceeds the workgroup).
+  constexpr int PER = C2T_MAX_CANDIDATES_DEV / NT;           // candidates per thread when T = 1
+  int tshift = 0;
+  while (tshift < 4 && (FK << (tshift + 1)) <= NT) ++tshift;
+  const int T = 1 << tshift, sub = tid & (T - 1), per = (FK + NT - 1) / NT, cand_stride = NT >> tshift;
+  // Everything this step reads from memory is requested up front, for all F*K slots, so that the
+  // step pays one memory round trip (the logits pass keeps the memory system saturated).
+  float my_z[PER], my_P[PER], my_H[PER]; int32_t my_tok[PER], my_par[PER];
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int i = (tid >> tshift) + k * cand_stride;
+    if (k < per && i < FK) {
+      const int64_t o = (int64_t)b * FK + i;
+      my_z[k] = ld_dev(s.c_z + o); my_tok[k] = ld_dev(s.c_tok + o);
+      my_P[k] = ld_dev(s.c_P + o); my_H[k] = ld_dev(s.c_H + o);
+      my_par[k] = s.fr_node[(int64_t)b * F + i / K];
     }
-    cz[i] = z; ctok[i] = tok; cP[i] = P32;
-    const int64_t o = (int64_t)b * FK + i;
-    s.c_tok[o] = tok; s.c_p[o] = p32; s.c_P[o] = P32; s.c_H[o] = rowBad[f] ? 0.f : rowH[f]; s.c_z[o] = z;
-    s.c_kept[o] = 0;
-    if (tok >= 0 && z > z_beta) { const int u = atomicAdd(&n_surv, 1); surv[u] = i; sz[u] = z; }
+  }
+  const uint32_t info = tid < F ? ld_dev(s.row_info + (int64_t)b * F + tid) : 0u;
+  const int nf = s.nf[layer & 1][b];
+  const int nn = s.n_nodes[b];
+  if (tid == 0) { n_surv = 0; flags_or = 0; }
+  for (int i = tid; i < ((FK + 31) & ~31); i += NT) sz[i] = -INFINITY;
+  __syncthreads();
+  if (tid < nf && info) atomicOr(&flags_or, (int)info);
+
+  // ---- first pruning: z > logit(beta) ----
+  const int ncand = nf * K;
+  int my_u[PER];                                             // own position in the survivor list, -1 = pruned
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int i = (tid >> tshift) + k * cand_stride;
+    my_u[k] = -1;
+    if (k < per && i < ncand && sub == 0) {
+      ctok[i] = my_tok[k];
+      if (my_tok[k] >= 0 && my_z[k] > z_beta) { const int u = atomicAdd(&n_surv, 1); surv[u] = i; sz[u] = my_z[k]; my_u[k] = u; }
+    }
   }
   __syncthreads();
 
   // ---- second pruning + budget: rank survivors by (z desc, token asc, slot asc) ----
   const int ns = n_surv;
   const int n_keep = max(0, min(min(F, N - nn), ns));
-  __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
-  __shared__ float new_P[SP_MAX_F];
-  for (int u = tid; u < ns; u += nt) {
-    const int i = surv[u];
-    const float z = sz[u]; const int tok = ctok[i];
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int i = (tid >> tshift) + k * cand_stride;
+    const bool mine = k < per && i < ncand;
+    const float z = my_z[k]; const int tok = my_tok[k];
+    const bool survivor = mine && tok >= 0 && z > z_beta;
     int rank = 0;
-    // survivors ahead of this one: larger z, or equal z and (token, slot) smaller
-    auto tie = [&](int v) {
-      const int j = surv[v];
-      if (j != i) { const int tj = ctok[j]; rank += (tj < tok) || (tj == tok && j < i); }
-    };
-    int v = 0;
-#pragma unroll 2
-    for (; v + 4 <= ns; v += 4) {
-      const float4 q = *(const float4*)(sz + v);
-      rank += (q.x > z) + (q.y > z) + (q.z > z) + (q.w > z);
-      if (q.x == z || q.y == z || q.z == z || q.w == z) {
-        if (q.x == z) tie(v);
-        if (q.y == z) tie(v + 1);
-        if (q.z == z) tie(v + 2);
-        if (q.w == z) tie(v + 3);
+    if (survivor) {
+      // survivors ahead of this one: larger z, or equal z and (token, slot) smaller.  sz is padded
+      // with -inf to a multiple of 32; 32 values per step, because the LDS is busy with the
+      // neighbouring workgroup's histogram and every dependent read is slow.
+      for (int v = sub * 32; v < ns; v += T * 32) {
+        float qa[32];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const float4 q = *(const float4*)(sz + v + 4 * t);
+          qa[4 * t] = q.x; qa[4 * t + 1] = q.y; qa[4 * t + 2] = q.z; qa[4 * t + 3] = q.w;
+        }
+        uint32_t eq = 0;
+#pragma unroll
+        for (int t = 0; t < 32; ++t) { rank += qa[t] > z; eq |= (qa[t] == z ? 1u : 0u) << t; }
+        while (eq) {                                           // ties in z: rare apart from the candidate itself
+          const int t = __ffs(eq) - 1; eq &= eq - 1;
+          const int j = surv[v + t];
+          if (j != i) { const int tj = ctok[j]; rank += (tj < tok) || (tj == tok && j < i); }
+        }
       }
     }
-    for (; v < ns; ++v) { const float zj = sz[v]; if (zj > z) ++rank; else if (zj == z) tie(v); }
-    if (rank < n_keep) {
-      const int f = i / K;
-      const int node = nn + rank;
-      const int64_t o = (int64_t)b * FK + i, t = (int64_t)b * N + node;
-      s.c_kept[o] = 1;
-      s.t_tok[t] = tok; s.t_parent[t] = parNode[f]; s.t_depth[t] = layer;
-      s.t_P[t] = cP[i]; s.t_H[t] = rowH[f]; s.t_z[t] = z;
-      new_tok[rank] = tok; new_pslot[rank] = f; new_node[rank] = node; new_P[rank] = cP[i];
+    // total over the T lanes of the candidate (every lane of the wave takes part)
+    if (tshift >= 1) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 2) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR2, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 3) rank += (int)dpp_u32<C2T_DPP_ROW_HALF_MIRROR, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 4) rank += (int)dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(0u, (uint32_t)rank);
+    if (mine && sub == 0) {
+      int kept = 0;
+      if (survivor && rank < n_keep) {
+        const int node = nn + rank;
+        const int64_t t = (int64_t)b * N + node;
+        kept = 1;
+        s.t_tok[t] = tok; s.t_parent[t] = my_par[k]; s.t_depth[t] = layer;
+        s.t_P[t] = my_P[k]; s.t_H[t] = my_H[k]; s.t_z[t] = z;
+        new_tok[rank] = tok; new_pslot[rank] = i / K; new_node[rank] = node; new_P[rank] = my_P[k];
+      }
+      s.c_kept[(int64_t)b * FK + i] = kept;
     }
   }
   __syncthreads();
@@ -237,12 +299,46 @@ __global__ __launch_bounds__(1024) void k_score_prune(
   }
   if (tid == 0) {
     s.n_nodes[b] = nn + n_keep;
-    s.n_frontier[b] = n_keep;
+    s.nf[(layer + 1) & 1][b] = n_keep;
     s.n_cand[b] = ncand;
-    if (any_bad) s.status[b] |= 1u;
-    if (any_slow) s.status[b] |= 2u;
+    if (flags_or) s.status[b] |= (uint32_t)flags_or;
     if (n_keep) atomicAdd(&s.layer_rows[layer + 1], n_keep);
   }
+}
+
+// Every thread's device-coherent stores are complete, then thread 0 takes a ticket: true for the
+// workgroup that took the last of `expected` (it resets the counter for the next layer).
+__device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
+  __shared__ int32_t sh_last;
+  wait_vector_memory();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
+    if (sh_last) st_dev(ticket, 0);
+  }
+  __syncthreads();
+  return sh_last != 0;
+}
+
+// Tail of the logits pass for the workgroup that owned (sequence b, frontier slot f, split): `rr`
+// holds its segment's result.  The workgroup that completes a row scores the row's candidates; the
+// workgroup that completes a sequence's last row prunes and appends.  Both overlap with the other
+// workgroups' streaming, so the whole layer is one launch.
+template <int NT>
+__device__ __forceinline__ void finish_layer(const TreeState& s, const ScoreParams& sp, int b, int f, int split,
+                                             int64_t row_launched, RowResult& rr, unsigned char* lds) {
+  const int tid = threadIdx.x, K = sp.K;
+  __syncthreads();                                           // rr is complete
+  if (sp.nsplit > 1) {
+    const int64_t po = row_launched * sp.nsplit + split;
+    if (tid < rr.part.n_top) { st_dev(sp.part_topv + po * K + tid, rr.topv[tid]); st_dev(sp.part_topi + po * K + tid, rr.topi[tid]); }
+    if (tid == 0) st_dev(sp.part + po, rr.part);
+    if (!last_arrival(s.row_tickets + (int64_t)b * sp.F + f, sp.nsplit)) return;
+    merge_row(sp, row_launched, rr, lds, (size_t)sp.lds_bytes);
+  }
+  score_row(s, sp, b, f, rr, (float*)lds);
+  if (!last_arrival(s.tickets + b, s.nf[sp.layer & 1][b])) return;
+  prune_sequence<NT>(s, sp, b, lds);
 }
 
 struct TreeOut {

@@ -22,13 +22,15 @@ namespace {
 constexpr size_t ALIGN = 256;
 static_assert(C2T_MAX_CANDIDATES == C2T_MAX_CANDIDATES_DEV && C2T_MAX_FRONTIER == SP_MAX_F && C2T_MAX_TOP_K == 64,
               "limits of the C ABI and of the kernels must agree");
-// Cell map of one workgroup.  bf16: two workgroups of 1024 threads must fit the CU's 160 KB, each with
-// the 32 KB histogram, 10.1 KB of static LDS and the map: 80 KB - 32 KB - 10336 B = 38816 B at most.
-constexpr int MAX_MAP_BYTES_BF16 = 38528;
+// Cell map of one workgroup.  bf16: four workgroups of 512 threads share the CU's 160 KB, each with the
+// 16 KB histogram, its static LDS (under 8 KB) and the map (2 bytes per 4 chunks): 16 KB at most.
+constexpr int HP_NT = 512;                     // workgroup size of the histogram kernel
+constexpr int MAX_MAP_BYTES_BF16 = 16 * 1024;
 constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
 constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
 constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
-constexpr int TARGET_WORKGROUPS = 512;         // two workgroups per CU; beyond that a split only adds epilogues
+constexpr int TARGET_WORKGROUPS = 256;         // a split adds an epilogue and a merge: only split while the CUs are not all busy
+constexpr int MAX_DEFAULT_SPLITS = 8;
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -46,9 +48,10 @@ int epc_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? 8 : 4; }
 int keybytes_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? 2 : 4; }
 int chunks_of(const c2t_config& c) { return (c.vocab + epc_of(c) - 1) / epc_of(c); }
 // fewest splits for which one workgroup's cell map fits its LDS budget
+int cpc_of(const c2t_config& c) { return c.logits_dtype == C2T_BF16 ? HP_CPC : 1; }   // chunks per map cell
 int min_splits(const c2t_config& c) {
-  const int max_cells = (c.logits_dtype == C2T_BF16 ? MAX_MAP_BYTES_BF16 : MAX_MAP_BYTES_F32) / keybytes_of(c);
-  return (chunks_of(c) + max_cells - 1) / max_cells;
+  const int max_chunks = (c.logits_dtype == C2T_BF16 ? MAX_MAP_BYTES_BF16 : MAX_MAP_BYTES_F32) / keybytes_of(c) * cpc_of(c);
+  return (chunks_of(c) + max_chunks - 1) / max_chunks;
 }
 
 int check_config(const c2t_config* c) {
@@ -117,7 +120,7 @@ namespace {
 int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
   const int nmin = min_splits(c);
   const int by_size = std::max(1, chunks_of(c) / (c.logits_dtype == C2T_BF16 ? HP_NT : NT_F32));   // at least one full sweep of the workgroup
-  const int64_t want = (TARGET_WORKGROUPS + rows - 1) / rows;
+  const int64_t want = std::min<int64_t>((TARGET_WORKGROUPS + rows - 1) / rows, MAX_DEFAULT_SPLITS);
   const int64_t cap = L.partial_slots / rows;
   const int64_t ns = std::min<int64_t>(std::min<int64_t>(want, by_size), cap);
   return (int)std::max<int64_t>(ns, nmin);
@@ -126,8 +129,16 @@ int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
 hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit,
                          hipStream_t s) {
   const c2t_config& c = x->cfg;
+  const int cpc = cpc_of(c);
   const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
-  const size_t map_lds = std::max<size_t>((size_t)cps * keybytes_of(c), (size_t)SEL_ELEM_CAP * 8);
+  const char* ev = getenv("C2T_HIST_NT");
+  const int hist_nt = ev ? atoi(ev) : HP_NT;
+  const int cells = c.logits_dtype == C2T_BF16
+                        ? (hist_nt == 1024 ? cells_in_segment<1024, HP_CPC>(cps) : cells_in_segment<HP_NT, HP_CPC>(cps))
+                        : cps;
+  const size_t map_lds = ((size_t)cells * keybytes_of(c) + 15) / 16 * 16;
+  // element list of the selection: (2K-1) cells of cpc chunks, 8 bytes per element
+  const size_t list_lds = (size_t)(2 * c.top_k - 1) * cpc * epc_of(c) * 8;
   const size_t score_lds = score_lds_bytes(c.hidden, c.max_frontier * c.top_k);
   const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
   ScoreParams sp;
@@ -135,21 +146,27 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
   sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta;
   if (c.logits_dtype == C2T_BF16) {
-    static bool lds_raised = false;       // static + dynamic LDS of this kernel exceeds the 64 KB default
-    if (!lds_raised) {
-      hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         HP_BINS * 4 + MAX_MAP_BYTES_BF16);
-      if (e != hipSuccess) return e;
-      lds_raised = true;
-    }
-    const size_t lds = std::max<size_t>((size_t)HP_BINS * 4 + map_lds, score_lds);
+    const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
     sp.lds_bytes = (int)lds;
-    const char* sv = getenv("C2T_STAGGER_US");
-    const int stagger_ticks = sv ? atoi(sv) * 100 : 0;
-    hipLaunchKernelGGL(k_logits_hist, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
-                       x->st, sp, stagger_ticks > 0 ? 512 : 0, stagger_ticks);
+    if (hist_nt == 1024) {
+      static size_t lds_raised = 48 * 1024;   // dynamic LDS the runtime allows this kernel so far
+      if (lds > lds_raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_raised = lds;
+      }
+      hipLaunchKernelGGL(k_logits_hist<1024>, dim3(grid), dim3(1024), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st, sp);
+    } else {
+      static size_t lds_raised = 48 * 1024;
+      if (lds > lds_raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist<HP_NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_raised = lds;
+      }
+      hipLaunchKernelGGL(k_logits_hist<HP_NT>, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st, sp);
+    }
   } else {
-    const size_t lds = std::max<size_t>(map_lds, score_lds);
+    const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
     sp.lds_bytes = (int)lds;
     hipLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, logits, stride, c.vocab,
                        cps, x->st, sp);

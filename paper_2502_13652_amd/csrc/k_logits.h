@@ -13,25 +13,42 @@
 //  * bf16 rows (the fast path): a bf16 logit has at most 65536 values, and all logits of
 //    practical rows lie in 32 binades, |x| in [2^-25, 2^7).  The streaming loop only COUNTS
 //    values: one LDS atomic per element into an 8192-bin histogram (sign, 5 exponent bits,
-//    7 mantissa bits).  Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v
+//    7 mantissa bits; two 16-bit counters per LDS word, overflow detected through the total).
+//    Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v
 //    are formed in fp64 from a table of e^v: exact counts, <= 8192 fp64 terms, independent
 //    of the order in which the elements were read.
 //  * any other row (fp32 logits; bf16 rows holding a logit outside the window, a zero, an
 //    infinity or a NaN): two passes over the segment with fp64 exponentials per element.
 //
-// Top-K without data-dependent work in the streaming loop: the loop records each chunk's
-// maximum ("cell key") in an LDS map.  Afterwards a bound tau <= K-th largest logit is known
+// Top-K without data-dependent work in the streaming loop: the loop records the maximum of each
+// cell as a "cell key" in an LDS map.  A cell is one chunk (fp32) or the four chunks a lane reads
+// in four consecutive sweeps of the workgroup (bf16: chunks i, i+NT, i+2NT, i+3NT of the segment).  Afterwards a bound tau <= K-th largest logit is known
 // (exactly, from the histogram; or as the K-th largest per-lane maximum), only cells whose
-// key reaches tau can hold a top-K element, and those few cells are re-read (16 bytes each)
-// and their elements ranked exactly by (logit desc, id asc).
+// key reaches tau can hold a top-K element, and those few cells are re-read and their elements
+// ranked exactly by (logit desc, id asc).
 #pragma once
 #include "k_common.h"
 #include "k_tree.h"
 
 namespace c2t {
 
-constexpr int SEL_CELL_CAP = 256;              // candidate cells kept per workgroup (>= 2*K)
-constexpr int SEL_ELEM_CAP = SEL_CELL_CAP * 8; // candidate elements (8 bytes each, overlaying the cell map)
+constexpr int SEL_CELL_CAP = 256;              // size of the candidate-cell list
+
+// LDS the selection may use once the cell list is built: the element list ((value, id), 8 bytes
+// an entry, overlaying histogram and cell map) and the number of cells a launch may keep:
+// min(SEL_CELL_CAP, NT / CPC, list entries / elements per cell), which the host keeps >= 2K - 1.
+struct SelectLds {
+  unsigned char* list;
+  int list_cap;       // entries
+  int cell_cap;
+};
+template <int NT, int CPC, int EPC>
+__device__ __forceinline__ SelectLds make_select_lds(unsigned char* base, int bytes) {
+  SelectLds s;
+  s.list = base; s.list_cap = bytes / 8;
+  s.cell_cap = min(min(SEL_CELL_CAP, NT / CPC), s.list_cap / (CPC * EPC));
+  return s;
+}
 
 template <int DT> struct LogitTraits;
 template <> struct LogitTraits<1> {     // bf16
@@ -74,89 +91,142 @@ __device__ __forceinline__ Segment make_segment(int V, int split, int cps) {
   return s;
 }
 
+// Cells of a segment of n chunks.  CPC = 4: sweep s of the workgroup reads chunks [s*NT, (s+1)*NT);
+// cell (s/4)*NT + t holds the chunks that lane t reads in sweeps 4*(s/4) .. 4*(s/4)+3.
+template <int NT, int CPC>
+__host__ __device__ inline int cells_in_segment(int n) {
+  if (CPC == 1) return n;
+  const int full = n / (4 * NT), rem = n - full * 4 * NT;
+  return full * NT + (rem < NT ? rem : NT);
+}
+// chunk j (0 <= j < CPC) of a cell, as an index into the segment; may lie past its end
+template <int NT, int CPC>
+__device__ __forceinline__ int chunk_of_cell(int cell, int j) {
+  if (CPC == 1) return cell;
+  const int grp = cell / NT, t = cell - grp * NT;
+  return grp * 4 * NT + j * NT + t;
+}
+
 // ---------------------------------------------------------------------------------------
 // Selection, shared by both paths.
 // ---------------------------------------------------------------------------------------
 
-// Cells whose key exceeds tau, plus the first `eq_limit` cells (in cell order) whose key equals
-// tau, are written to cell_list.  Returns false (list untouched) if they do not fit.
+// Cells whose key reaches tau (exceeds it, if strict) are pushed to cell_list, in any order.
+// Returns how many there are; if that is more than cell_cap the list is incomplete.
 template <int DT, int NT>
-__device__ __forceinline__ bool build_cell_list(const typename LogitTraits<DT>::key_t* map, int ncell, float tau,
-                                                int eq_limit, int32_t* cell_list, int32_t (*scan_tmp)[NT / WAVE],
-                                                int* n_cells_out) {
+__device__ __forceinline__ int list_cells(const typename LogitTraits<DT>::key_t* map, int ncells, float tau, bool strict,
+                                          int cell_cap, int32_t* cell_list, int32_t* sh_n) {
   typedef LogitTraits<DT> T;
-  constexpr int NW = NT / WAVE;
-  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
-  const int cpl = (ncell + NT - 1) / NT;                    // contiguous cells per lane
-  const int s0 = min(tid * cpl, ncell), s1 = min(s0 + cpl, ncell);
-  int n_gt = 0, n_eq = 0;
-#pragma unroll 1
-  for (int s = s0; s < s1; ++s) {
-    const float kv = T::from_key(map[s]);
-    n_gt += kv > tau; n_eq += kv == tau;
-  }
-  const int ig = wave_scan_incl(n_gt), ie = wave_scan_incl(n_eq);
-  if (lane == WAVE - 1) { scan_tmp[0][wid] = ig; scan_tmp[1][wid] = ie; }
+  if (threadIdx.x == 0) *sh_n = 0;
   __syncthreads();
-  int og = 0, oe = 0, tg = 0, te = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    if (w < wid) { og += scan_tmp[0][w]; oe += scan_tmp[1][w]; }
-    tg += scan_tmp[0][w]; te += scan_tmp[1][w];
-  }
-  const int take_eq = min(te, eq_limit);
-  const bool fits = tg + take_eq <= SEL_CELL_CAP;
-  if (fits) {
-    int pg = og + ig - n_gt, pe = oe + ie - n_eq;          // exclusive prefixes in cell order
 #pragma unroll 1
-    for (int s = s0; s < s1; ++s) {
-      const float kv = T::from_key(map[s]);
-      if (kv > tau) cell_list[pg++] = s;
-      else if (kv == tau) { if (pe < take_eq) cell_list[tg + pe] = s; ++pe; }
+  for (int c = threadIdx.x; c < ncells; c += NT) {
+    const float kv = T::from_key(map[c]);
+    if (strict ? kv > tau : kv >= tau) {
+      const int slot = atomicAdd(sh_n, 1);
+      if (slot < cell_cap) cell_list[slot] = c;
     }
   }
   __syncthreads();
-  *n_cells_out = tg + take_eq;
-  return fits;
+  return *sh_n;
 }
 
-// Re-read the listed cells, keep their elements >= tau, rank them exactly by (logit desc,
-// id asc) and write the best K.  The element list overlays the cell map (no longer needed).
-template <int DT, int NT>
-__device__ __forceinline__ int finish_topk(const uint4* __restrict__ rowp, int c0, int V, int K, float tau,
-                                           const int32_t* cell_list, int n_cells, unsigned char* dyn_lds,
-                                           int32_t* sh_cnt, float* topv, int32_t* topi) {
+// Re-read the listed cells (CPC chunks each, one chunk per thread) and append their elements that
+// reach tau (exceed it, if strict) to the element list.  *sh_cnt must be 0 on entry (set before
+// a barrier); ends with a barrier.
+template <int DT, int NT, int CPC>
+__device__ __forceinline__ void collect_cells(const uint4* __restrict__ rowp, int c0, int c1, int V, float tau, bool strict,
+                                              const int32_t* cell_list, int n_cells, const SelectLds& sel, int32_t* sh_cnt) {
   typedef LogitTraits<DT> T;
   const int tid = threadIdx.x;
-  float* el_v = (float*)dyn_lds;
-  int32_t* el_i = (int32_t*)(dyn_lds + SEL_ELEM_CAP * 4);
-  if (tid == 0) *sh_cnt = 0;
-  int my_cell = -1;
+  float* el_v = (float*)sel.list;
+  int32_t* el_i = (int32_t*)(sel.list + (size_t)sel.list_cap * 4);
+  int my_chunk = -1;
   uint4 q = make_uint4(0, 0, 0, 0);
-  if (tid < n_cells) { my_cell = c0 + cell_list[tid]; q = rowp[my_cell]; }      // n_cells <= SEL_CELL_CAP <= NT
-  __syncthreads();
-  if (my_cell >= 0) {
+  if (tid < n_cells * CPC) {                                 // n_cells <= cell_cap <= NT / CPC
+    const int ch = c0 + chunk_of_cell<NT, CPC>(cell_list[tid / CPC], tid % CPC);
+    if (ch < c1) { my_chunk = ch; q = rowp[ch]; }
+  }
+  __syncthreads();                                           // the cell map is dead: the list may overlay it
+  if (my_chunk >= 0) {
     float x[T::EPC];
     T::unpack(q, x);
 #pragma unroll
     for (int j = 0; j < T::EPC; ++j) {
-      const int id = my_cell * T::EPC + j;
-      if (id < V && x[j] >= tau) {
+      const int id = my_chunk * T::EPC + j;
+      if (id < V && (strict ? x[j] > tau : x[j] >= tau)) {
         const int slot = atomicAdd(sh_cnt, 1);
-        el_v[slot] = x[j]; el_i[slot] = id;
+        if (slot < sel.list_cap) { el_v[slot] = x[j]; el_i[slot] = id; }
       }
     }
   }
   __syncthreads();
-  const int n_el = *sh_cnt;
+}
+
+// Massive ties: append the `need` lowest-id elements equal to tau, found by sweeping the segment in
+// id order (one chunk per thread and sweep, prefix counts across the workgroup) until enough are seen.
+template <int DT, int NT>
+__device__ __forceinline__ void tie_scan(const uint4* __restrict__ rowp, const Segment& sg, int V, float tau, int need,
+                                         const SelectLds& sel, int32_t* sh_cnt, int32_t (*scan_tmp)[NT / WAVE]) {
+  typedef LogitTraits<DT> T;
+  constexpr int NW = NT / WAVE;
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  float* el_v = (float*)sel.list;
+  int32_t* el_i = (int32_t*)(sel.list + (size_t)sel.list_cap * 4);
+  int found = 0;                                             // uniform
+#pragma unroll 1
+  for (int base = sg.c0; base < sg.c1 && found < need; base += NT) {
+    const int g = base + tid;
+    uint32_t hit = 0;
+    if (g < sg.c1) {
+      float x[T::EPC];
+      T::unpack(rowp[g], x);
+#pragma unroll
+      for (int j = 0; j < T::EPC; ++j) hit |= (g * T::EPC + j < V && x[j] == tau ? 1u : 0u) << j;
+    }
+    const int cnt = __popc(hit);
+    const int incl = wave_scan_incl(cnt);
+    if (lane == WAVE - 1) scan_tmp[0][wid] = incl;
+    __syncthreads();
+    int before = found + incl - cnt, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { if (w < wid) before += scan_tmp[0][w]; total += scan_tmp[0][w]; }
+    while (hit && before < need) {
+      const int j = __ffs(hit) - 1; hit &= hit - 1;
+      const int slot = atomicAdd(sh_cnt, 1);
+      if (slot < sel.list_cap) { el_v[slot] = tau; el_i[slot] = g * T::EPC + j; }
+      ++before;
+    }
+    found += total;
+    __syncthreads();
+  }
+}
+
+// Rank the element list exactly by (logit desc, id asc) and write the best K.
+template <int NT>
+__device__ __forceinline__ int rank_list(int K, const SelectLds& sel, const int32_t* sh_cnt, float* topv, int32_t* topi) {
+  const int tid = threadIdx.x;
+  const float* el_v = (const float*)sel.list;
+  const int32_t* el_i = (const int32_t*)(sel.list + (size_t)sel.list_cap * 4);
+  const int n_el = min(*sh_cnt, sel.list_cap);
 #pragma unroll 1
   for (int e = tid; e < n_el; e += NT) {
     const float v = el_v[e]; const int id = el_i[e];
     int rank = 0;
-#pragma unroll 4
-    for (int o = 0; o < n_el; ++o) {
-      const float vo = el_v[o];
-      rank += (vo > v) || (vo == v && el_i[o] < id);
+    // eight values per step (entries past n_el are masked): every dependent LDS read is slow while
+    // the neighbouring workgroups fill their histograms
+#pragma unroll 1
+    for (int o = 0; o < n_el; o += 8) {
+      const float4 qa = *(const float4*)(el_v + o), qb = *(const float4*)(el_v + o + 4);
+      const float vo[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+      uint32_t eq = 0;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const bool in = o + t < n_el;
+        rank += in && vo[t] > v; eq |= (in && vo[t] == v ? 1u : 0u) << t;
+      }
+      eq &= ~(e >= o && e < o + 8 ? 1u << (e - o) : 0u);    // not the element itself
+      while (eq) { const int t = __ffs(eq) - 1; eq &= eq - 1; rank += el_i[o + t] < id; }
     }
     if (rank < K) { topv[rank] = v; topi[rank] = id; }
   }
@@ -201,13 +271,16 @@ __device__ __forceinline__ float block_max(float v, float* red /*[NT/WAVE]*/) {
 // ---------------------------------------------------------------------------------------
 // Generic path: two passes over the segment, fp64 exponentials.  Any dtype, any values.
 // ---------------------------------------------------------------------------------------
-template <int DT, int NT>
+// map_lds: one key per cell.
+template <int DT, int NT, int CPC>
 __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, const Segment sg,
-                                unsigned char* dyn_lds, RowResult* rr, uint32_t info_flags) {
+                                unsigned char* map_lds, const SelectLds sel, RowResult* rr, uint32_t info_flags) {
   typedef LogitTraits<DT> T;
   typedef typename T::key_t key_t;
   constexpr int NW = NT / WAVE;
-  key_t* map = (key_t*)dyn_lds;
+  static_assert(CPC == 1 || CPC == 4, "a cell is one chunk or four sweeps of a lane");
+  key_t* map = (key_t*)map_lds;
+  const int ncells = cells_in_segment<NT, CPC>(sg.ncell);
   __shared__ double red_d[2][NW], sum_d[2];
   __shared__ float red_f[NW];
   __shared__ uint32_t lane_keys[NT];
@@ -222,7 +295,9 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
   // pass 1: cell keys, lane maxima, NaN / +inf
   float M = -INFINITY;
   bool bad = false, any = false;
-  for (int g = sg.c0 + tid; g < sg.c1; g += NT) {
+  float cell_max = -INFINITY;
+  int sweep = 0;
+  for (int g = sg.c0 + tid; g < sg.c1; g += NT, ++sweep) {
     const uint4 q = rowp[g];
     float x[T::EPC];
     T::unpack(q, x);
@@ -233,7 +308,11 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
       if (j < nv) { bad |= !(x[j] < INFINITY); cm = fmaxf(cm, x[j]); }
     }
     M = fmaxf(M, cm);
-    map[g - sg.c0] = T::to_key(cm);
+    if (CPC == 1) map[g - sg.c0] = T::to_key(cm);
+    else {
+      cell_max = fmaxf(cell_max, cm);
+      if ((sweep & 3) == 3 || g + NT >= sg.c1) { map[(sweep >> 2) * NT + tid] = T::to_key(cell_max); cell_max = -INFINITY; }
+    }
     any = true;
   }
   lane_keys[tid] = any ? sortable_key(M) : 0u;
@@ -274,12 +353,13 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
   __syncthreads();
   uint32_t tau_key = sh_tau;
   float tau = tau_key ? key_to_float(tau_key) : -INFINITY;
-  int n_cells = 0;
-  if (!build_cell_list<DT, NT>(map, sg.ncell, tau, K, cell_list, scan_tmp, &n_cells)) {
+  bool ties = false;
+  int n_cells = list_cells<DT, NT>(map, ncells, tau, false, sel.cell_cap, cell_list, &sh_cnt);
+  if (n_cells > sel.cell_cap) {
     // Too many cells reach the bound (maxima clustered in few lanes): take the exact K-th
     // largest cell key by radix select over the whole map; fewer than K cells exceed it.
-    const int cpl = (sg.ncell + NT - 1) / NT;
-    const int s0 = min(tid * cpl, sg.ncell), s1 = min(s0 + cpl, sg.ncell);
+    const int cpl = (ncells + NT - 1) / NT;
+    const int s0 = min(tid * cpl, ncells), s1 = min(s0 + cpl, ncells);
     uint32_t prefix = 0, care = 0;
     int k = K;
     for (int bit = 31; bit >= 0; --bit) {
@@ -297,9 +377,17 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
       care = cmask;
     }
     tau = prefix ? key_to_float(prefix) : -INFINITY;
-    build_cell_list<DT, NT>(map, sg.ncell, tau, K, cell_list, scan_tmp, &n_cells);   // now <= 2K-1 cells
+    n_cells = list_cells<DT, NT>(map, ncells, tau, false, sel.cell_cap, cell_list, &sh_cnt);
+    if (n_cells > sel.cell_cap) {                            // massive ties at tau: the cells above it, then a tie scan
+      n_cells = list_cells<DT, NT>(map, ncells, tau, true, sel.cell_cap, cell_list, &sh_cnt);
+      ties = true;
+    }
   }
-  const int n_top = finish_topk<DT, NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, dyn_lds, &sh_cnt, rr->topv, rr->topi);
+  if (tid == 0) sh_cnt = 0;
+  __syncthreads();
+  collect_cells<DT, NT, CPC>(rowp, sg.c0, sg.c1, V, tau, ties, cell_list, n_cells, sel, &sh_cnt);
+  if (ties) tie_scan<DT, NT>(rowp, sg, V, tau, K, sel, &sh_cnt, scan_tmp);
+  const int n_top = rank_list<NT>(K, sel, &sh_cnt, rr->topv, rr->topi);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = (double)m; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = seg_bad ? 0 : n_top; r.flags = (seg_bad ? 1u : 0u) | info_flags;
@@ -314,7 +402,8 @@ __device__ __forceinline__ void end_of_sequence(const TreeState& st, const Score
 }
 
 // grid: rows_launched * nsplit workgroups of NT threads.
-// Dynamic LDS: max(cps * sizeof(key_t), SEL_ELEM_CAP * 8, score_lds_bytes) bytes.
+// Dynamic LDS (sp.lds_bytes): the cell map (cps keys), reused for the element list of the selection
+// ((2K-1) * EPC entries of 8 bytes at least) and by the tail.
 template <int DT, int NT>
 __global__ __launch_bounds__(NT) void k_logits_generic(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, TreeState st, ScoreParams sp) {
@@ -330,37 +419,33 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   const Segment sg = make_segment<T::EPC>(V, split, cps);
   __shared__ RowResult rr;
   if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
-  else generic_segment<DT, NT>(rowp, V, K, sg, dyn_lds, &rr, 0u);
+  else generic_segment<DT, NT, 1>(rowp, V, K, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
   finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds);         // split records are indexed by launched row
 }
 
 // ---------------------------------------------------------------------------------------
 // bf16 fast path: value histogram.
 // ---------------------------------------------------------------------------------------
-constexpr int HP_NT = 1024;
-constexpr int HP_NW = HP_NT / WAVE;
 constexpr int HP_BINS = 8192;                 // sign(1) | exponent mod 32 (5) | mantissa (7)
-constexpr int HP_BPL = HP_BINS / HP_NT;       // bins per lane in the epilogue
+constexpr int HP_WORDS = HP_BINS / 2;         // LDS words: low half counts +|v|, high half counts -|v|
+constexpr int HP_CPC = 4;                     // chunks per cell of the map: four sweeps of a lane
 constexpr uint32_t HP_MAG_LO = 102u << 7;     // |x| >= 2^-25
 constexpr uint32_t HP_MAG_SPAN = 32u << 7;    // 32 binades: |x| < 2^7
+constexpr uint32_t HP_WORD_ROT = HP_MAG_LO & (HP_WORDS - 1);   // word of magnitude index i: (i + ROT) mod 4096
+constexpr uint32_t HP_F16_NEG_INF2 = 0xFC00FC00u;              // identity of the packed maximum
 
-__device__ __forceinline__ uint32_t hp_bin_of_code(uint32_t code16) {
-  return (code16 & 0xFFFu) | ((code16 >> 3) & 0x1000u);
-}
-// value-ordered rank r in [0, 8192): larger r = larger value.  r -> bf16 code and bin.
+// value-ordered rank r in [0, 8192): larger r = larger value.  r -> bf16 code.
 __device__ __forceinline__ uint32_t hp_code_of_rank(int r) {
   const uint32_t s = r < 4096 ? 1u : 0u;
   const uint32_t magidx = s ? (uint32_t)(4095 - r) : (uint32_t)(r - 4096);
   return (s << 15) | (HP_MAG_LO + magidx);
 }
-
-__device__ __forceinline__ int hp_rank_of_code(uint32_t code16) {
-  const int magidx = (int)((code16 & 0x7fffu) - HP_MAG_LO);
-  return (code16 & 0x8000u) ? 4095 - magidx : 4096 + magidx;
+__device__ __forceinline__ float hp_value_of_mag(uint32_t magidx, bool negative) {
+  return __uint_as_float(((HP_MAG_LO + magidx) << 16) | (negative ? 0x80000000u : 0u));
 }
 
-// e^v for every value of the window, fp64, in value order (index = rank), so that the 8
-// ranks a lane owns in the epilogue are one contiguous 64-byte read.  Filled once per context.
+// e^v for every value of the window, fp64, in value order (index = rank), so that the ranks a
+// lane owns in the epilogue are two contiguous runs.  Filled once per context.
 __global__ void k_init_exp_table(double* __restrict__ tab_e) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r < HP_BINS) tab_e[r] = exp((double)__uint_as_float(hp_code_of_rank(r) << 16));
@@ -380,15 +465,14 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 
 struct HistLane {
   uint32_t mag_max = 0u;            // packed running max of |code| (two halves): NaN, inf and |x| >= 2^7 show here
-  float M = -INFINITY;              // running maximum
+  uint32_t M2 = HP_F16_NEG_INF2;    // packed running maximum of the bf16 patterns (compared as fp16 patterns)
   int n_tiny = 0;                   // logits with |x| < 2^-25 (zeros included): e^x = 1 + x to fp64 accuracy
   double s_tiny = 0.0;              // their sum
 };
 
 // One element at a time: used for chunks that hold a logit below the window and for a row's
-// partial last chunk.
-__device__ __forceinline__ void hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist,
-                                              uint16_t* __restrict__ map, int cell) {
+// partial last chunk.  Returns the maximum of the valid elements as a packed pattern.
+__device__ __forceinline__ uint32_t hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
   float x[8];
   LogitTraits<1>::unpack(q, x);
   float cm = -INFINITY;
@@ -398,14 +482,15 @@ __device__ __forceinline__ void hist_elements(const uint4& q, int n_valid, HistL
     a.mag_max = pk_max_u16(a.mag_max, mag);
     cm = fmaxf(cm, x[j]);
     if (mag < HP_MAG_LO) { a.n_tiny += 1; a.s_tiny += (double)x[j]; }
-    else atomicAdd(&hist[hp_bin_of_code(code)], 1u);
+    else atomicAdd(&hist[code & (HP_WORDS - 1)], (code & 0x8000u) ? 0x10000u : 1u);
   }
-  a.M = fmaxf(a.M, cm);
-  map[cell] = (uint16_t)(__float_as_uint(cm) >> 16);
+  const uint32_t c16 = __float_as_uint(cm) >> 16;
+  return c16 | (c16 << 16);
 }
 
-__device__ __forceinline__ void hist_chunk(const uint4& q, HistLane& a, uint32_t* __restrict__ hist,
-                                           uint16_t* __restrict__ map, int cell) {
+// Counts the chunk's values; returns the chunk maximum as a packed pattern (both halves <= max,
+// one of them equal to it).
+__device__ __forceinline__ uint32_t hist_chunk(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
   // |code| range of the chunk; NaN and infinities have the largest magnitudes
   uint32_t mx = a.mag_max, mn = 0x7fff7fffu;
@@ -414,143 +499,167 @@ __device__ __forceinline__ void hist_chunk(const uint4& q, HistLane& a, uint32_t
     const uint32_t mag = w[j] & 0x7fff7fffu;
     mx = pk_max_u16(mx, mag); mn = pk_min_u16(mn, mag);
   }
-  a.mag_max = mx;
   constexpr uint32_t LO2 = HP_MAG_LO | (HP_MAG_LO << 16);
-  if (pk_min_u16(mn, LO2) != LO2) {           // rare: a logit below the window
-    hist_elements(q, 8, a, hist, map, cell);
-    return;
-  }
-  // chunk maximum: inside the window bf16 bit patterns order exactly like fp16 bit patterns
-  // (above it the row leaves this path anyway)
-  const uint32_t m2 = pk_max_f16(pk_max_f16(w[0], w[1]), pk_max_f16(w[2], w[3]));
-  const float cm = fmaxf(bf16_lo(m2), bf16_hi(m2));
-  a.M = fmaxf(a.M, cm);
-  map[cell] = (uint16_t)(__float_as_uint(cm) >> 16);
+  uint32_t pat;
+  if (pk_min_u16(mn, LO2) != LO2 || n_valid != 8) {          // rare: a logit below the window, or the row's last chunk
+    pat = hist_elements(q, n_valid, a, hist);
+  } else {
+    a.mag_max = mx;
+    // inside the window bf16 bit patterns order exactly like fp16 bit patterns (above it the
+    // row leaves this path anyway)
+    pat = pk_max_f16(pk_max_f16(w[0], w[1]), pk_max_f16(w[2], w[3]));
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t ih = ((w[j] >> 16) & 0xFFFu) | ((w[j] >> 19) & 0x1000u);
-    const uint32_t il = (w[j] & 0xFFFu) | ((w[j] >> 3) & 0x1000u);
-    atomicAdd(&hist[ih], 1u);
-    atomicAdd(&hist[il], 1u);
+    for (int j = 0; j < 4; ++j) {
+      // +1 into the low half for a positive value, into the high half for a negative one
+      atomicAdd(&hist[(w[j] >> 16) & (HP_WORDS - 1)], __umul24(w[j] >> 31, 0xffffu) + 1u);
+      atomicAdd(&hist[w[j] & (HP_WORDS - 1)], __umul24((w[j] >> 15) & 1u, 0xffffu) + 1u);
+    }
   }
+  a.M2 = pk_max_f16(a.M2, pat);
+  return pat;
 }
 
-// One (row, split) segment on the histogram path, run by a whole workgroup of HP_NT threads.
-// hist: HP_BINS counters, map_lds: max(cps * 2, SEL_ELEM_CAP * 8) bytes (cell map / element list).
+// One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
+// hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
+template <int NT>
 __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, const Segment& sg,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
-                                             unsigned char* map_lds, RowResult* rr) {
+                                             unsigned char* map_lds, const SelectLds& sel, RowResult* rr) {
+  constexpr int NW = NT / WAVE;
+  constexpr int WPL = HP_WORDS / NT;                   // words per lane in the epilogue (8 at 512 threads)
+  static_assert(NW <= 16 && WPL % 4 == 0, "one DPP row holds the per-wave partials; a lane reads whole 16-byte runs");
   uint16_t* map = (uint16_t*)map_lds;
-  __shared__ double red_d[2][HP_NW], sum_d[2];
-  __shared__ float red_f[HP_NW], red_v[HP_NW];
-  __shared__ uint32_t red_u[HP_NW];
+  __shared__ double red_d[2][NW], sum_d[2];
+  __shared__ float red_v[NW];
+  __shared__ uint32_t red_u[NW], red_m[NW];
   __shared__ int32_t sh_ntiny;
   __shared__ double sh_stiny;
   __shared__ int32_t cell_list[SEL_CELL_CAP];
-  __shared__ int32_t scan_tmp[2][HP_NW];
+  __shared__ int32_t scan_tmp[2][NW];
   __shared__ int32_t sh_cnt, sh_ncell, sh_tau_rank, sh_n_gt;
 
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
 
 #pragma unroll
-  for (int j = 0; j < HP_BPL; ++j) hist[tid + j * HP_NT] = 0u;
+  for (int j = 0; j < WPL; ++j) hist[tid + j * NT] = 0u;
   if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_ntiny = 0; sh_stiny = 0.0; }
   __syncthreads();
 
   // ---------------- streaming loop: count values, record cell maxima ----------------
   HistLane a;
-  const int c1_full = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;
   {
-    // four chunks per lane in flight: a workgroup that streams alone (its neighbour on the CU is
-    // in its epilogue) still covers the HBM latency.  Unrolled by four so that each buffer is
+    // four chunks per lane in flight: a workgroup that streams while its neighbours on the CU are
+    // in their epilogues still covers the HBM latency.  Unrolled by four so that each buffer is
     // refilled right after it has been counted, without register copies.
     int g = sg.c0 + tid;
+    const int c1 = sg.c1, tail = sg.tail_chunk, tv = sg.tail_valid;
     const uint4* dummy = rowp + sg.c0;                   // in-bounds address for lanes past their last chunk
-#define C2T_LOAD(i) (*((i) < c1_full ? rowp + (i) : dummy))
-    uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + HP_NT), qc = C2T_LOAD(g + 2 * HP_NT), qd = C2T_LOAD(g + 3 * HP_NT);
-    for (; g + 3 * HP_NT < c1_full; g += 4 * HP_NT) {    // whole groups of four: one straight-line body
-      hist_chunk(qa, a, hist, map, g - sg.c0);
-      qa = C2T_LOAD(g + 4 * HP_NT);
-      hist_chunk(qb, a, hist, map, g + HP_NT - sg.c0);
-      qb = C2T_LOAD(g + 5 * HP_NT);
-      hist_chunk(qc, a, hist, map, g + 2 * HP_NT - sg.c0);
-      qc = C2T_LOAD(g + 6 * HP_NT);
-      hist_chunk(qd, a, hist, map, g + 3 * HP_NT - sg.c0);
-      qd = C2T_LOAD(g + 7 * HP_NT);
+#define C2T_LOAD(i) (*((i) < c1 ? rowp + (i) : dummy))
+#define C2T_COUNT(q, i) hist_chunk(q, (i) == tail ? tv : 8, a, hist)
+    uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + NT), qc = C2T_LOAD(g + 2 * NT), qd = C2T_LOAD(g + 3 * NT);
+    uint16_t* mp = map + tid;
+    // groups of four sweeps in which every lane has a chunk
+    for (int it = (c1 - sg.c0) / (4 * NT); it > 0; --it, g += 4 * NT, mp += NT) {
+      uint32_t key = C2T_COUNT(qa, g);
+      qa = C2T_LOAD(g + 4 * NT);
+      key = pk_max_f16(key, C2T_COUNT(qb, g + NT));
+      qb = C2T_LOAD(g + 5 * NT);
+      key = pk_max_f16(key, C2T_COUNT(qc, g + 2 * NT));
+      qc = C2T_LOAD(g + 6 * NT);
+      key = pk_max_f16(key, C2T_COUNT(qd, g + 3 * NT));
+      qd = C2T_LOAD(g + 7 * NT);
+      *mp = (uint16_t)pk_max_f16(key, key >> 16);
     }
-    if (g < c1_full) hist_chunk(qa, a, hist, map, g - sg.c0);                           // up to three left
-    if (g + HP_NT < c1_full) hist_chunk(qb, a, hist, map, g + HP_NT - sg.c0);
-    if (g + 2 * HP_NT < c1_full) hist_chunk(qc, a, hist, map, g + 2 * HP_NT - sg.c0);
+    if (g < c1) {                                        // the last, partial group: up to four chunks of this lane
+      uint32_t key = C2T_COUNT(qa, g);
+      if (g + NT < c1) key = pk_max_f16(key, C2T_COUNT(qb, g + NT));
+      if (g + 2 * NT < c1) key = pk_max_f16(key, C2T_COUNT(qc, g + 2 * NT));
+      if (g + 3 * NT < c1) key = pk_max_f16(key, C2T_COUNT(qd, g + 3 * NT));
+      *mp = (uint16_t)pk_max_f16(key, key >> 16);
+    }
+#undef C2T_COUNT
 #undef C2T_LOAD
   }
-  if (sg.tail_chunk >= 0 && ((sg.tail_chunk - sg.c0) % HP_NT) == tid)    // only tail_valid elements exist
-    hist_elements(rowp[sg.tail_chunk], sg.tail_valid, a, hist, map, sg.tail_chunk - sg.c0);
   if (a.n_tiny) { atomicAdd(&sh_ntiny, a.n_tiny); atomicAdd(&sh_stiny, a.s_tiny); }
 
-  // the lane's slice of the e^v table (ranks 8191-8t-7 ... 8191-8t, ascending): issued now so
-  // that its latency hides behind the first barrier
-  double ev[HP_BPL];
+  // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  Its slices of
+  // the e^v table (ranks 4096 + i for +|v|, 4095 - i for -|v|) are issued now so that their latency
+  // hides behind the barrier.
+  double evp[WPL], evn[WPL];
   {
-    const double* tp = tab_e + (HP_BINS - HP_BPL * (tid + 1));
+    const double* tp = tab_e + (HP_WORDS + WPL * tid);
+    const double* tn = tab_e + (HP_WORDS - WPL * (tid + 1));
 #pragma unroll
-    for (int j = 0; j < HP_BPL; ++j) ev[j] = tp[j];
+    for (int j = 0; j < WPL; ++j) { evp[j] = tp[j]; evn[j] = tn[WPL - 1 - j]; }
   }
   // per-wave: magnitude range and maximum
   {
-    uint32_t mx = a.mag_max;
-    mx = wave_reduce_u32(mx, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
-    const float mw = wave_max(a.M);
-    if (lane == 0) { red_u[wid] = mx; red_f[wid] = mw; }
+    const uint32_t mx = wave_reduce_u32(a.mag_max, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
+    const uint32_t m2 = wave_reduce_u32(a.M2, HP_F16_NEG_INF2, [](uint32_t x, uint32_t y) { return pk_max_f16(x, y); });
+    if (lane == 0) { red_u[wid] = mx; red_m[wid] = m2; }
   }
   __syncthreads();                                     // histogram, cell map and wave results complete
 
-  // ---------------- lane t owns the value ranks 8191-8t ... 8191-8t-7 (descending) ----------------
-  // Z = sum n_v e^v and S = sum n_v (v - m) e^v.  S is accumulated against the largest value seen
-  // so far at each level (lane, wave, workgroup), so every term has the same sign and nothing
-  // cancels: rows whose entropy is tiny keep their relative accuracy.
+  // ---------------- Z = sum n_v e^v and S = sum n_v (v - m) e^v ----------------
+  // S is accumulated against the largest value seen so far at each level (lane, wave, workgroup),
+  // so every term has the same sign and nothing cancels: rows whose entropy is tiny keep their
+  // relative accuracy.
   double Z = 0.0, S = 0.0;
-  int lane_total = 0;
+  int lane_pos = 0, lane_neg = 0;
   float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
-  uint32_t n[HP_BPL];
+  uint32_t cw[WPL];                                     // low half: count of +|v_j|, high half: count of -|v_j|
   {
+    const uint32_t w0 = ((uint32_t)(WPL * tid) + HP_WORD_ROT) & (HP_WORDS - 1);   // WPL-aligned: no wrap inside
 #pragma unroll
-    for (int j = 0; j < HP_BPL; ++j) {
-      n[j] = hist[hp_bin_of_code(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)))];
-      lane_total += (int)n[j];
+    for (int j = 0; j < WPL; j += 4) {
+      const uint4 t = *(const uint4*)(hist + w0 + j);
+      cw[j] = t.x; cw[j + 1] = t.y; cw[j + 2] = t.z; cw[j + 3] = t.w;
     }
 #pragma unroll
-    for (int j = HP_BPL - 1; j >= 0; --j)
-      if (n[j]) vtop = __uint_as_float(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)) << 16);
-    const double vt = lane_total ? (double)vtop : 0.0;
+    for (int j = 0; j < WPL; ++j) { lane_pos += (int)(cw[j] & 0xffffu); lane_neg += (int)(cw[j] >> 16); }
 #pragma unroll
-    for (int j = 0; j < HP_BPL; ++j) {
-      const double v = (double)__uint_as_float(hp_code_of_rank(HP_BINS - 1 - (tid * HP_BPL + j)) << 16);
-      const double t = (double)n[j] * ev[HP_BPL - 1 - j];          // n * e^v (0 for an empty bin)
-      Z += t; S += (v - vt) * t;
-      __builtin_amdgcn_sched_barrier(0);                           // one bin at a time: keeps live registers low
+    for (int j = WPL - 1; j >= 0; --j)                  // lowest of the negative values last
+      if (cw[j] >> 16) vtop = hp_value_of_mag(WPL * tid + j, true);
+#pragma unroll
+    for (int j = 0; j < WPL; ++j)                       // highest of the positive values last
+      if (cw[j] & 0xffffu) vtop = hp_value_of_mag(WPL * tid + j, false);
+    const double vt = (lane_pos | lane_neg) ? (double)vtop : 0.0;
+#pragma unroll
+    for (int j = 0; j < WPL; ++j) {
+      const double vp = (double)hp_value_of_mag(WPL * tid + j, false);
+      const double tp = (double)(cw[j] & 0xffffu) * evp[j];        // n * e^v (0 for an empty bin)
+      Z += tp; S += (vp - vt) * tp;
+      const double tn = (double)(cw[j] >> 16) * evn[j];
+      Z += tn; S += (-vp - vt) * tn;
+      __builtin_amdgcn_sched_barrier(0);                           // one bin pair at a time: keeps live registers low
     }
   }
   const float vw = wave_max(vtop);                      // -inf only if the whole wave owns empty bins
-  if (lane_total) S += ((double)vtop - (double)vw) * Z;
+  if (lane_pos | lane_neg) S += ((double)vtop - (double)vw) * Z;
   Z = wave_sum(Z); S = wave_sum(S);
-  const int incl = wave_scan_incl(lane_total);
+  const int incl_p = wave_scan_incl(lane_pos), incl_n = wave_scan_incl(lane_neg);
   if (lane == 0) { red_d[0][wid] = Z; red_d[1][wid] = S; red_v[wid] = vw; }
-  if (lane == WAVE - 1) scan_tmp[0][wid] = incl;
+  if (lane == WAVE - 1) { scan_tmp[0][wid] = incl_p; scan_tmp[1][wid] = incl_n; }
   __syncthreads();
 
-  uint32_t mx = 0u;
-  float m = red_f[0];
+  uint32_t mx = 0u, m2 = HP_F16_NEG_INF2;
 #pragma unroll
-  for (int w = 0; w < HP_NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m = fmaxf(m, red_f[w]); }
+  for (int w = 0; w < NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m2 = pk_max_f16(m2, red_m[w]); }
   const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16);
+  const float m = fmaxf(bf16_lo(m2), bf16_hi(m2));      // exact whenever the row stays on this path
   const int n_tiny = sh_ntiny;
-  if (wid == 0) {                                       // lanes 0..15 hold one wave's sums each; fixed order
+  int before_p = 0, before_n = 0, tot_p = 0, tot_n = 0; // counts in lower lanes / in the whole segment
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wid) { before_p += scan_tmp[0][w]; before_n += scan_tmp[1][w]; }
+    tot_p += scan_tmp[0][w]; tot_n += scan_tmp[1][w];
+  }
+  if (wid == 0) {                                       // lanes 0..NW-1 hold one wave's sums each; fixed order
     double tz = 0.0, ts = 0.0;
-    if (lane < HP_NW && red_d[0][lane] > 0.0) {
+    if (lane < NW && red_d[0][lane] > 0.0) {
       tz = red_d[0][lane];
       ts = red_d[1][lane] + ((double)red_v[lane] - (double)m) * tz;
     }
-    static_assert(HP_NW == 16, "one DPP row holds the per-wave partials");
     tz += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(ts);
     tz += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(ts);
     tz += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(ts);
@@ -563,27 +672,40 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       sum_d[0] = tz; sum_d[1] = ts;
     }
   }
-  // tau = exact K-th largest logit: first rank (from the top) where the running count reaches K
+  // tau = exact K-th largest logit: first value (from the top) where the running count reaches K.
+  // Descending value order: positive values from the highest lane down, then negative values from
+  // lane 0 up.
   {
-    int above = incl - lane_total;                       // elements in higher-valued lanes
+    const int above_p = tot_p - (before_p + incl_p);                   // positive elements in higher lanes
+    if (above_p < K && above_p + lane_pos >= K) {                      // at most one lane
+      int run = above_p;
 #pragma unroll
-    for (int w = 0; w < HP_NW; ++w) if (w < wid) above += scan_tmp[0][w];
-    if (above < K && above + lane_total >= K) {          // exactly one lane
-      int run = above;
+      for (int j = WPL - 1; j >= 0; --j) {
+        const int n = (int)(cw[j] & 0xffffu);
+        if (run < K && run + n >= K) { sh_tau_rank = HP_WORDS + WPL * tid + j; sh_n_gt = run; }
+        run += n;
+      }
+    }
+    const int above_n = tot_p + before_n + incl_n - lane_neg;          // everything positive, and negatives in lower lanes
+    if (above_n < K && above_n + lane_neg >= K) {
+      int run = above_n;
 #pragma unroll
-      for (int j = 0; j < HP_BPL; ++j) {
-        if (run < K && run + (int)n[j] >= K) { sh_tau_rank = HP_BINS - 1 - (tid * HP_BPL + j); sh_n_gt = run; }
-        run += (int)n[j];
+      for (int j = 0; j < WPL; ++j) {
+        const int n = (int)(cw[j] >> 16);
+        if (run < K && run + n >= K) { sh_tau_rank = HP_WORDS - 1 - (WPL * tid + j); sh_n_gt = run; }
+        run += n;
       }
     }
   }
   __syncthreads();
-  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, infinities, NaN), or if
-  // logits below it exist and the K-th largest logit is not a positive window value (then they
+  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, infinities, NaN), if a
+  // 16-bit counter overflowed (the total is then off by a multiple of 65535 or 65536), or if logits
+  // below the window exist and the K-th largest logit is not a positive window value (then they
   // could be among the top K, which the histogram cannot rank).
-  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || (n_tiny > 0 && sh_tau_rank < HP_BINS / 2)) {
+  const int n_elems = (sg.tail_chunk >= 0 ? (sg.ncell - 1) * 8 + sg.tail_valid : sg.ncell * 8);
+  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS)) {
     __syncthreads();
-    generic_segment<1, HP_NT>(rowp, V, K, sg, map_lds, rr, 2u);
+    generic_segment<1, NT, HP_CPC>(rowp, V, K, sg, map_lds, sel, rr, 2u);
     return;
   }
   float tau = -INFINITY;
@@ -591,23 +713,34 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   if (sh_tau_rank >= 0) { tau = __uint_as_float(hp_code_of_rank(sh_tau_rank) << 16); eq_limit = K - sh_n_gt; }
 
   // ---------------- cells that can hold a top-K element ----------------
-  // Only a lane whose own maximum reaches tau owns such a cell (its cells are tid, tid+NT, ...).
   // Fewer than K cells exceed tau; cells equal to tau are all taken when they fit (the exact
-  // ranking below keeps the lowest ids), else the ordered scan picks the first eq_limit of them.
-  if (a.M >= tau) {
+  // ranking below keeps the lowest ids).
+  const int ncells = cells_in_segment<NT, HP_CPC>(sg.ncell);
 #pragma unroll 1
-    for (int cix = tid; cix < sg.ncell; cix += HP_NT) {
-      if (__uint_as_float((uint32_t)map[cix] << 16) >= tau) {
+  for (int c8 = tid * 8; c8 < ncells; c8 += NT * 8) {    // eight keys per read (the map is padded to 16 bytes)
+    const uint4 kq = *(const uint4*)(map + c8);
+    const uint32_t kw[4] = {kq.x, kq.y, kq.z, kq.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float kv = (j & 1) ? bf16_hi(kw[j >> 1]) : bf16_lo(kw[j >> 1]);
+      if (c8 + j < ncells && kv >= tau) {
         const int slot = atomicAdd(&sh_ncell, 1);
-        if (slot < SEL_CELL_CAP) cell_list[slot] = cix;
+        if (slot < sel.cell_cap) cell_list[slot] = c8 + j;
       }
     }
   }
+  if (tid == 0) sh_cnt = 0;
   __syncthreads();
   int n_cells = sh_ncell;
-  if (n_cells > SEL_CELL_CAP)                            // massive ties at tau
-    build_cell_list<1, HP_NT>(map, sg.ncell, tau, eq_limit, cell_list, scan_tmp, &n_cells);
-  const int n_top = finish_topk<1, HP_NT>(rowp, sg.c0, V, K, tau, cell_list, n_cells, map_lds, &sh_cnt, rr->topv, rr->topi);
+  const bool ties = n_cells > sel.cell_cap;                  // massive ties at tau: the cells above it, then a tie scan
+  if (ties) {
+    n_cells = list_cells<1, NT>(map, ncells, tau, true, sel.cell_cap, cell_list, &sh_ncell);
+    if (tid == 0) sh_cnt = 0;
+    __syncthreads();
+  }
+  collect_cells<1, NT, HP_CPC>(rowp, sg.c0, sg.c1, V, tau, ties, cell_list, n_cells, sel, &sh_cnt);
+  if (ties) tie_scan<1, NT>(rowp, sg, V, tau, eq_limit, sel, &sh_cnt, scan_tmp);
+  const int n_top = rank_list<NT>(K, sel, &sh_cnt, rr->topv, rr->topi);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
@@ -615,24 +748,15 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   }
 }
 
-// grid: rows_launched * nsplit workgroups of HP_NT threads.
-// Dynamic LDS: [HP_BINS counters | max(cps * 2, SEL_ELEM_CAP * 8) bytes of cell map / element list];
-// the scoring step of the sequence's last workgroup reuses all of it.
-__global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
+// grid: rows_launched * nsplit workgroups of NT threads.
+// Dynamic LDS (sp.lds_bytes): [HP_WORDS counters | cell map, padded to 16 bytes]; the selection's
+// element list and the tail reuse all of it.
+template <int NT>
+__global__ __launch_bounds__(NT, 8) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
-    TreeState st, ScoreParams sp, int stagger_wgs, int stagger_ticks) {
+    TreeState st, ScoreParams sp) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   const int nsplit = sp.nsplit, K = sp.K;
-  // Two workgroups share a compute unit.  Started together they stream together and then run their
-  // epilogues together, leaving the memory system idle; delaying the second one of the first round
-  // makes the pairs alternate (later workgroups inherit the phase of the one they replace).
-  if ((int)blockIdx.x < stagger_wgs) {
-    const uint32_t lds_base = __builtin_amdgcn_s_getreg((7 << 11) | (0 << 6) | 6);   // HW_REG_LDS_ALLOC, LDS_BASE
-    if (lds_base != 0) {
-      const uint64_t t0 = wall_clock64();
-      for (int spin = 0; spin < 64 && (int64_t)(wall_clock64() - t0) < stagger_ticks; ++spin) __builtin_amdgcn_s_sleep(64);
-    }
-  }
   const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
   const int b = rl / sp.rows_per_seq, f = rl % sp.rows_per_seq;
   const int nf = st.nf[sp.layer & 1][b];
@@ -642,8 +766,9 @@ __global__ __launch_bounds__(HP_NT, 8) void k_logits_hist(
   const Segment sg = make_segment<8>(V, split, cps);
   __shared__ RowResult rr;
   if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
-  else hist_segment(rowp, V, K, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_BINS * 4, &rr);
-  finish_layer<HP_NT>(st, sp, b, f, split, rl, rr, dyn_lds);
+  else hist_segment<NT>(rowp, V, K, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
+                        make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
+  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds);
 }
 
 // Plain streaming read: the practical HBM ceiling.

@@ -155,7 +155,7 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
         if (e != hipSuccess) return e;
         lds_raised = lds;
       }
-      hipLaunchKernelGGL(k_logits_hist<1024>, dim3(grid), dim3(1024), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st, sp);
+      hipLaunchKernelGGL(k_logits_hist<1024>, dim3(grid), dim3(1024), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st.cls, x->st, sp);
     } else {
       static size_t lds_raised = 48 * 1024;
       if (lds > lds_raised) {
@@ -163,13 +163,13 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
         if (e != hipSuccess) return e;
         lds_raised = lds;
       }
-      hipLaunchKernelGGL(k_logits_hist<HP_NT>, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st, sp);
+      hipLaunchKernelGGL(k_logits_hist<HP_NT>, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st.cls, x->st, sp);
     }
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
     sp.lds_bytes = (int)lds;
     hipLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, logits, stride, c.vocab,
-                       cps, x->st, sp);
+                       cps, x->st.cls, x->st, sp);
   }
   return hipGetLastError();
 }

@@ -406,7 +406,8 @@ __device__ __forceinline__ void end_of_sequence(const TreeState& st, const Score
 // ((2K-1) * EPC entries of 8 bytes at least) and by the tail.
 template <int DT, int NT>
 __global__ __launch_bounds__(NT) void k_logits_generic(
-    const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, TreeState st, ScoreParams sp) {
+    const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const float* __restrict__ cls,
+    TreeState st, ScoreParams sp) {
   typedef LogitTraits<DT> T;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   const int nsplit = sp.nsplit, K = sp.K;
@@ -420,7 +421,7 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   __shared__ RowResult rr;
   if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
   else generic_segment<DT, NT, 1>(rowp, V, K, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
-  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds);         // split records are indexed by launched row
+  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
 }
 
 // ---------------------------------------------------------------------------------------
@@ -754,7 +755,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 template <int NT>
 __global__ __launch_bounds__(NT, 8) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
-    TreeState st, ScoreParams sp) {
+    const float* __restrict__ cls, TreeState st, ScoreParams sp) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   const int nsplit = sp.nsplit, K = sp.K;
   const int split = blockIdx.x % nsplit, rl = blockIdx.x / nsplit;
@@ -768,7 +769,7 @@ __global__ __launch_bounds__(NT, 8) void k_logits_hist(
   if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
   else hist_segment<NT>(rowp, V, K, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
-  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds);
+  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);
 }
 
 // Plain streaming read: the practical HBM ceiling.

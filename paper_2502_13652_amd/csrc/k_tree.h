@@ -94,11 +94,15 @@ __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_lau
   const RowPartial* rp = sp.part + row_launched * nsplit;
   const float* tv = sp.part_topv + row_launched * nsplit * K;
   const int32_t* ti = sp.part_topi + row_launched * nsplit * K;
-  if (tid == 0) {
-    double R = -INFINITY; uint32_t fl = 0;
-    for (int q = 0; q < nsplit; ++q) { R = fmax(R, ld_dev(&rp[q].ref)); fl |= ld_dev(&rp[q].flags); }
+  if (tid < WAVE) {                                          // wave 0: the sums, one split per lane and step
+    const int lane = tid;
+    float Rf = -INFINITY; uint32_t fl = 0;                   // ref holds a logit: exact as a float
+    for (int q = lane; q < nsplit; q += WAVE) { Rf = fmaxf(Rf, (float)ld_dev(&rp[q].ref)); fl |= ld_dev(&rp[q].flags); }
+    Rf = wave_max(Rf);
+    fl = wave_reduce_u32(fl, 0u, [](uint32_t x, uint32_t y) { return x | y; });
+    const double R = (double)Rf;
     double Z = 0.0, S = 0.0;
-    for (int q = 0; q < nsplit; ++q) {
+    for (int q = lane; q < nsplit; q += WAVE) {
       const RowPartial pq = ld_dev(rp + q);
       if (pq.Z > 0.0 && pq.ref > -INFINITY) {
         const double da = pq.a - R, dl = pq.ref - R;         // re-reference to the row maximum R; dl <= 0
@@ -106,7 +110,8 @@ __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_lau
         Z += pq.Z * sc; S += (pq.S + dl * pq.Z) * sc;
       }
     }
-    rr.part.ref = R; rr.part.a = R; rr.part.Z = Z; rr.part.S = S; rr.part.flags = fl; rr.part.n_top = 0;
+    Z = wave_sum(Z); S = wave_sum(S);
+    if (lane == 0) { rr.part.ref = R; rr.part.a = R; rr.part.Z = Z; rr.part.S = S; rr.part.flags = fl; rr.part.n_top = 0; }
   }
   // An entry's merged rank = number of entries of the row's lists ahead of it.
   const int per_row = nsplit * K;
@@ -159,13 +164,13 @@ __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_lau
 
 // ---- row level: entropy (Eq. 2), generation and joint probabilities (Eq. 1), classifier logit
 // (Eq. 3) of the row's K candidates, from the complete row result in `rr`.  One lane per candidate.
+// `w`: the classifier parameters in global memory, read-only for the whole kernel: every lane
+// reads the same addresses, so the loads are scalar and touch neither LDS nor the vector memory path.
 __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams& sp, int b, int f, const RowResult& rr,
-                                          float* w /* LDS, 5h+1 floats */) {
+                                          const float* __restrict__ w) {
   const int tid = threadIdx.x, K = sp.K;
-  const float parP = s.fr_P[(int64_t)b * sp.F + f];                          // requested together with the weights
-  for (int i = tid; i < 5 * sp.h + 1; i += blockDim.x) w[i] = s.cls[i];     // one coalesced read, then LDS broadcasts
-  __syncthreads();
   if (tid >= K) return;
+  const float parP = s.fr_P[(int64_t)b * sp.F + f];
   const double R = rr.part.ref, Z = rr.part.Z;
   const uint32_t fl = rr.part.flags;
   const bool bad = (fl & 1u) != 0 || !(Z > 0.0) || !(R > -INFINITY) || !(R < INFINITY);
@@ -326,7 +331,8 @@ __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
 // workgroups' streaming, so the whole layer is one launch.
 template <int NT>
 __device__ __forceinline__ void finish_layer(const TreeState& s, const ScoreParams& sp, int b, int f, int split,
-                                             int64_t row_launched, RowResult& rr, unsigned char* lds) {
+                                             int64_t row_launched, RowResult& rr, unsigned char* lds,
+                                             const float* __restrict__ cls) {
   const int tid = threadIdx.x, K = sp.K;
   __syncthreads();                                           // rr is complete
   if (sp.nsplit > 1) {
@@ -336,7 +342,7 @@ __device__ __forceinline__ void finish_layer(const TreeState& s, const ScorePara
     if (!last_arrival(s.row_tickets + (int64_t)b * sp.F + f, sp.nsplit)) return;
     merge_row(sp, row_launched, rr, lds, (size_t)sp.lds_bytes);
   }
-  score_row(s, sp, b, f, rr, (float*)lds);
+  score_row(s, sp, b, f, rr, cls);
   if (!last_arrival(s.tickets + b, s.nf[sp.layer & 1][b])) return;
   prune_sequence<NT>(s, sp, b, lds);
 }

@@ -78,14 +78,6 @@ struct RowResult {
   int32_t topi[64];
 };
 
-// LDS the tail needs: per sequence 3 arrays of F*K (padded to 4) 4-byte entries (token, survivor
-// index, survivor z padded to 32); per row the 5h+1 classifier weights; the row merge stages nsplit*K (value, id)
-// pairs when they fit.
-__host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
-  const size_t a = ((size_t)2 * ((FK + 3) & ~3) + ((FK + 31) & ~31)) * 4, b = (size_t)(5 * h + 1) * 4;
-  return a > b ? a : b;
-}
-
 // ---- row level, splits > 1: combine the row's split records (fp64) and top lists into `rr`.
 // Run by the workgroup that delivered the row's last split; `lds`/`lds_bytes` is free scratch.
 __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_launched, RowResult& rr,
@@ -193,107 +185,174 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
 
 // ---- sequence level: both prunings of Sec. 4.2 with the node budget, tree append, next frontier.
 // Run by one whole workgroup once every row of the sequence has been scored.
+//
+// Survivors of the first pruning are compacted into LDS lists (z, token, candidate index).  Only the
+// n_keep best of them matter: when the list is long, a 4096-bin histogram over the top 12 bits of
+// the order-preserving key of z finds the bin that holds the n_keep-th largest z, and the list is
+// cut down to the survivors from that bin upwards before the exact ranking.  The ranking gives each
+// survivor to T = 2^tshift lanes, which split the list between them and read 32 values per step
+// (the LDS is busy with the neighbouring workgroups' histograms: dependent reads are slow).
+constexpr int PRUNE_HIST_WORDS = 2048;        // 4096 bins, two 16-bit counters per word
+constexpr int PRUNE_PRESELECT_MIN = 128;      // shorter lists are ranked directly
+
+__host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
+  (void)h;
+  return ((size_t)3 * ((FK + 31) & ~31) + PRUNE_HIST_WORDS) * 4;
+}
+
 template <int NT>
 __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScoreParams& sp, int b, unsigned char* lds) {
+  constexpr int NW = NT / WAVE;
   const int F = sp.F, K = sp.K, N = sp.N, layer = sp.layer;
   const float z_beta = sp.z_beta;
-  const int FK = F * K, FKp = (FK + 3) & ~3;
-  int32_t* ctok = (int32_t*)lds;
-  int32_t* surv = ctok + FKp;
-  float* sz = (float*)(surv + FKp);                        // z of the survivors, contiguous, 16-byte aligned
-  __shared__ int32_t n_surv, flags_or;
+  const int FK = F * K, FKp = (FK + 31) & ~31;
+  float* sz = (float*)lds;                                   // survivors: z, token, candidate index
+  int32_t* stok = (int32_t*)(sz + FKp);
+  int32_t* sidx = stok + FKp;
+  uint32_t* hist = (uint32_t*)(sidx + FKp);
+  __shared__ int32_t n_surv, n_red, flags_or, sel_bin;
+  __shared__ int32_t scan_w[NW];
   __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
   __shared__ float new_P[SP_MAX_F];
 
-  const int tid = threadIdx.x;
-  // T = 2^tshift consecutive lanes share a candidate and split the survivor list between them
-  // (T = 1 and several candidates per thread when F*K exceeds the workgroup).
-  constexpr int PER = C2T_MAX_CANDIDATES_DEV / NT;           // candidates per thread when T = 1
-  int tshift = 0;
-  while (tshift < 4 && (FK << (tshift + 1)) <= NT) ++tshift;
-  const int T = 1 << tshift, sub = tid & (T - 1), per = (FK + NT - 1) / NT, cand_stride = NT >> tshift;
-  // Everything this step reads from memory is requested up front, for all F*K slots, so that the
-  // step pays one memory round trip (the logits pass keeps the memory system saturated).
-  float my_z[PER], my_P[PER], my_H[PER]; int32_t my_tok[PER], my_par[PER];
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  // the candidates' z and tokens are requested up front for all F*K slots: one memory round trip
+  constexpr int PER = C2T_MAX_CANDIDATES_DEV / NT;           // candidates per thread
+  const int per = (FK + NT - 1) / NT;
+  float my_z[PER]; int32_t my_tok[PER];
 #pragma unroll
   for (int k = 0; k < PER; ++k) {
-    const int i = (tid >> tshift) + k * cand_stride;
+    const int i = tid + k * NT;
     if (k < per && i < FK) {
       const int64_t o = (int64_t)b * FK + i;
       my_z[k] = ld_dev(s.c_z + o); my_tok[k] = ld_dev(s.c_tok + o);
-      my_P[k] = ld_dev(s.c_P + o); my_H[k] = ld_dev(s.c_H + o);
-      my_par[k] = s.fr_node[(int64_t)b * F + i / K];
     }
   }
   const uint32_t info = tid < F ? ld_dev(s.row_info + (int64_t)b * F + tid) : 0u;
   const int nf = s.nf[layer & 1][b];
   const int nn = s.n_nodes[b];
-  if (tid == 0) { n_surv = 0; flags_or = 0; }
-  for (int i = tid; i < ((FK + 31) & ~31); i += NT) sz[i] = -INFINITY;
+  if (tid == 0) { n_surv = 0; n_red = 0; flags_or = 0; sel_bin = 0; }
+  for (int i = tid; i < PRUNE_HIST_WORDS; i += NT) hist[i] = 0u;
   __syncthreads();
   if (tid < nf && info) atomicOr(&flags_or, (int)info);
 
   // ---- first pruning: z > logit(beta) ----
   const int ncand = nf * K;
-  int my_u[PER];                                             // own position in the survivor list, -1 = pruned
 #pragma unroll
   for (int k = 0; k < PER; ++k) {
-    const int i = (tid >> tshift) + k * cand_stride;
-    my_u[k] = -1;
-    if (k < per && i < ncand && sub == 0) {
-      ctok[i] = my_tok[k];
-      if (my_tok[k] >= 0 && my_z[k] > z_beta) { const int u = atomicAdd(&n_surv, 1); surv[u] = i; sz[u] = my_z[k]; my_u[k] = u; }
+    const int i = tid + k * NT;
+    if (k < per && i < ncand) {
+      s.c_kept[(int64_t)b * FK + i] = 0;
+      if (my_tok[k] >= 0 && my_z[k] > z_beta) {
+        const int u = atomicAdd(&n_surv, 1);
+        sz[u] = my_z[k]; stok[u] = my_tok[k]; sidx[u] = i;
+        const uint32_t bin = sortable_key(my_z[k]) >> 20;
+        atomicAdd(&hist[bin >> 1], (bin & 1u) ? 0x10000u : 1u);
+      }
     }
   }
+  wait_vector_memory();                                      // the zeros are written before any thread stores a one
   __syncthreads();
 
   // ---- second pruning + budget: rank survivors by (z desc, token asc, slot asc) ----
-  const int ns = n_surv;
+  int ns = n_surv;
   const int n_keep = max(0, min(min(F, N - nn), ns));
+  if (n_keep > 0 && ns > PRUNE_PRESELECT_MIN) {
+    // bin of the n_keep-th largest z: thread t owns words 2047-4t .. 2047-4t-3 (bins descending)
+    constexpr int WPT = PRUNE_HIST_WORDS / NT;
+    uint32_t w[WPT]; int c = 0;
 #pragma unroll
-  for (int k = 0; k < PER; ++k) {
-    const int i = (tid >> tshift) + k * cand_stride;
-    const bool mine = k < per && i < ncand;
-    const float z = my_z[k]; const int tok = my_tok[k];
-    const bool survivor = mine && tok >= 0 && z > z_beta;
-    int rank = 0;
-    if (survivor) {
-      // survivors ahead of this one: larger z, or equal z and (token, slot) smaller.  sz is padded
-      // with -inf to a multiple of 32; 32 values per step, because the LDS is busy with the
-      // neighbouring workgroup's histogram and every dependent read is slow.
-      for (int v = sub * 32; v < ns; v += T * 32) {
-        float qa[32];
+    for (int j = 0; j < WPT; ++j) { w[j] = hist[PRUNE_HIST_WORDS - 1 - (tid * WPT + j)]; c += (int)(w[j] & 0xffffu) + (int)(w[j] >> 16); }
+    const int incl = wave_scan_incl(c);
+    if (lane == WAVE - 1) scan_w[wid] = incl;
+    __syncthreads();
+    int above = incl - c;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const float4 q = *(const float4*)(sz + v + 4 * t);
-          qa[4 * t] = q.x; qa[4 * t + 1] = q.y; qa[4 * t + 2] = q.z; qa[4 * t + 3] = q.w;
-        }
-        uint32_t eq = 0;
+    for (int v = 0; v < NW; ++v) if (v < wid) above += scan_w[v];
+    if (above < n_keep && above + c >= n_keep) {             // exactly one thread
+      int run = above;
 #pragma unroll
-        for (int t = 0; t < 32; ++t) { rank += qa[t] > z; eq |= (qa[t] == z ? 1u : 0u) << t; }
-        while (eq) {                                           // ties in z: rare apart from the candidate itself
-          const int t = __ffs(eq) - 1; eq &= eq - 1;
-          const int j = surv[v + t];
-          if (j != i) { const int tj = ctok[j]; rank += (tj < tok) || (tj == tok && j < i); }
-        }
+      for (int j = 0; j < WPT; ++j) {
+        const int word = PRUNE_HIST_WORDS - 1 - (tid * WPT + j);
+        const int hi = (int)(w[j] >> 16), lo = (int)(w[j] & 0xffffu);
+        if (run < n_keep && run + hi >= n_keep) sel_bin = 2 * word + 1;
+        run += hi;
+        if (run < n_keep && run + lo >= n_keep) sel_bin = 2 * word;
+        run += lo;
       }
     }
-    // total over the T lanes of the candidate (every lane of the wave takes part)
-    if (tshift >= 1) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(0u, (uint32_t)rank);
-    if (tshift >= 2) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR2, 0xf>(0u, (uint32_t)rank);
-    if (tshift >= 3) rank += (int)dpp_u32<C2T_DPP_ROW_HALF_MIRROR, 0xf>(0u, (uint32_t)rank);
-    if (tshift >= 4) rank += (int)dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(0u, (uint32_t)rank);
-    if (mine && sub == 0) {
-      int kept = 0;
-      if (survivor && rank < n_keep) {
-        const int node = nn + rank;
-        const int64_t t = (int64_t)b * N + node;
-        kept = 1;
-        s.t_tok[t] = tok; s.t_parent[t] = my_par[k]; s.t_depth[t] = layer;
-        s.t_P[t] = my_P[k]; s.t_H[t] = my_H[k]; s.t_z[t] = z;
-        new_tok[rank] = tok; new_pslot[rank] = i / K; new_node[rank] = node; new_P[rank] = my_P[k];
+    __syncthreads();
+    // cut the list down, in place: read, barrier, write
+    const int cut = sel_bin;
+    float rz[PER]; int32_t rt[PER], ri[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int u = tid + k * NT;
+      rz[k] = -INFINITY; rt[k] = 0; ri[k] = -1;
+      if (u < ns) { rz[k] = sz[u]; rt[k] = stok[u]; ri[k] = sidx[u]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      if (ri[k] >= 0 && (int)(sortable_key(rz[k]) >> 20) >= cut) {
+        const int u = atomicAdd(&n_red, 1);
+        sz[u] = rz[k]; stok[u] = rt[k]; sidx[u] = ri[k];
       }
-      s.c_kept[(int64_t)b * FK + i] = kept;
+    }
+    __syncthreads();
+    ns = n_red;
+  }
+  if (n_keep > 0) {
+    int tshift = 0;
+    while (tshift < 4 && (ns << (tshift + 1)) <= NT) ++tshift;
+    const int T = 1 << tshift, sub = tid & (T - 1), ustride = NT >> tshift;
+#pragma unroll 1
+    for (int u0 = 0; u0 < ns; u0 += ustride) {               // uniform trip count: every lane meets in the DPP sums
+      const int u = u0 + (tid >> tshift);
+      const bool mine = u < ns;
+      const float z = mine ? sz[u] : 0.f;
+      const int tok = mine ? stok[u] : 0, i = mine ? sidx[u] : 0;
+      // what an appended node needs, requested before the ranking so that the latency overlaps it
+      float P = 0.f, H = 0.f; int par = -1;
+      if (mine && sub == 0) {
+        const int64_t o = (int64_t)b * FK + i;
+        P = ld_dev(s.c_P + o); H = ld_dev(s.c_H + o); par = s.fr_node[(int64_t)b * F + i / K];
+      }
+      int rank = 0;
+      if (mine) {
+        for (int v = sub * 32; v < ns; v += T * 32) {        // entries past ns are masked
+          float qa[32];
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const float4 q = *(const float4*)(sz + v + 4 * t);
+            qa[4 * t] = q.x; qa[4 * t + 1] = q.y; qa[4 * t + 2] = q.z; qa[4 * t + 3] = q.w;
+          }
+          uint32_t eq = 0;
+#pragma unroll
+          for (int t = 0; t < 32; ++t) {
+            const bool in = v + t < ns;
+            rank += in && qa[t] > z; eq |= (in && qa[t] == z ? 1u : 0u) << t;
+          }
+          if (u >= v && u < v + 32) eq &= ~(1u << (u - v));  // not the survivor itself
+          while (eq) {                                         // ties in z: rare
+            const int t = __ffs(eq) - 1; eq &= eq - 1;
+            const int tj = stok[v + t], ij = sidx[v + t];
+            rank += (tj < tok) || (tj == tok && ij < i);
+          }
+        }
+      }
+      if (tshift >= 1) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(0u, (uint32_t)rank);
+      if (tshift >= 2) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR2, 0xf>(0u, (uint32_t)rank);
+      if (tshift >= 3) rank += (int)dpp_u32<C2T_DPP_ROW_HALF_MIRROR, 0xf>(0u, (uint32_t)rank);
+      if (tshift >= 4) rank += (int)dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(0u, (uint32_t)rank);
+      if (mine && sub == 0 && rank < n_keep) {
+        const int node = nn + rank, f = i / K;
+        const int64_t o = (int64_t)b * FK + i, t = (int64_t)b * N + node;
+        s.c_kept[o] = 1;
+        s.t_tok[t] = tok; s.t_parent[t] = par; s.t_depth[t] = layer;
+        s.t_P[t] = P; s.t_H[t] = H; s.t_z[t] = z;
+        new_tok[rank] = tok; new_pslot[rank] = f; new_node[rank] = node; new_P[rank] = P;
+      }
     }
   }
   __syncthreads();

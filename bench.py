@@ -1,10 +1,12 @@
 """Benchmark of the C2T tree-construction hot path on one MI355X.
 
 A step is one whole draft phase over one batch of synthetic logits: reset, max_depth x
-expand_layer (logits pass + score/prune), finalize_tree, with every input resident in HBM.
+expand_layer (one launch per layer: logits pass, row scoring and sequence pruning in the same
+kernel), finalize_tree, with every input resident in HBM.
 Prints ONE JSON line: whole-job throughput in draft-tree nodes scored per second, the HBM
-roofline of the logits-pass kernel (timed with HIP events on its own stream inside the timed
-region) and the CPU oracle timed on a bounded sample of the same workload.
+roofline of the layer kernel (timed with HIP events on its own stream inside the timed region;
+its algorithmic bytes are the logits rows it reads) and the CPU oracle timed on a bounded sample
+of the same workload.
 """
 import argparse
 import json
@@ -108,7 +110,7 @@ def main():
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "k_logits_pass", "launches": int(a.steps * D),
+                     "kernel": "k_logits_hist<512>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>", "launches": int(a.steps * D),
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),
                      "full_layer_gbps": float(np.mean([p["gbps"] for p, f in zip(per_layer, full) if f])) if full.any() else None,

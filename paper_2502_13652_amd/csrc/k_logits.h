@@ -72,6 +72,14 @@ template <> struct LogitTraits<0> {     // fp32
   static __device__ __forceinline__ float from_key(key_t k) { return k; }
 };
 
+// A logits chunk is read once per layer: a non-temporal load keeps the stream from evicting what
+// the workgroups reuse (the e^v table, the classifier) from the L2.
+typedef uint32_t c2t_uint4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  const c2t_uint4v v = __builtin_nontemporal_load((const c2t_uint4v*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Range of chunks a (row, split) workgroup owns.
 struct Segment {
   int c0, c1;        // chunks [c0, c1)
@@ -555,7 +563,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     int g = sg.c0 + tid;
     const int c1 = sg.c1, tail = sg.tail_chunk, tv = sg.tail_valid;
     const uint4* dummy = rowp + sg.c0;                   // in-bounds address for lanes past their last chunk
-#define C2T_LOAD(i) (*((i) < c1 ? rowp + (i) : dummy))
+#define C2T_LOAD(i) load_stream((i) < c1 ? rowp + (i) : dummy)
 #define C2T_COUNT(q, i) hist_chunk(q, (i) == tail ? tv : 8, a, hist)
     uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + NT), qc = C2T_LOAD(g + 2 * NT), qd = C2T_LOAD(g + 3 * NT);
     uint16_t* mp = map + tid;

@@ -45,6 +45,14 @@ def adversarial_rows(V, rng, bf16):
     add("sprinkled_tiny", tn)
     lowhigh = -20 + rng.standard_normal(V); lowhigh[V // 2:] += 60       # reference must be raised mid-row
     add("late_large", lowhigh)
+    if V > 70000:
+        # one value held by exactly 65535 / 65536 logits: the largest count a 16-bit histogram
+        # counter holds, and the smallest one that overflows it
+        for n_same in (65535, 65536):
+            r = 3 * rng.standard_normal(V); r[rng.choice(V, n_same, replace=False)] = -0.75
+            add("same_value_%d" % n_same, r)
+            r = 3 * rng.standard_normal(V); r[rng.choice(V, n_same, replace=False)] = 4.0   # ties reach the top K
+            add("same_top_value_%d" % n_same, r)
     return names, np.stack(rows)
 
 

@@ -46,7 +46,10 @@ def main():
     B, V, F, K, D, N, h = (cfg[k] for k in ("B", "V", "F", "K", "D", "N", "h"))
     esz = 4 if cfg["dtype"] == "f32" else 2
     cls = W.classifier(cfg, W.classifier_seed(a.workload))
-    layers = [W.logits_layer(cfg, l, device=dev) for l in range(D)]
+    # Small configurations are generated with the CPU generator, the stream the classifier seed was
+    # chosen on (torch's CPU and GPU generators differ; a GPU-generated cfg3 tree dies at the root).
+    gen = "cpu" if B * F * V * D * esz <= (256 << 20) else dev
+    layers = [W.logits_layer(cfg, l, device=gen).to(dev) for l in range(D)]
     ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"], device=dev)
     ctx.set_classifier(*cls)
     if a.splits:

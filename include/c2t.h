@@ -72,7 +72,9 @@ typedef struct {
   int32_t logits_dtype; /* C2T_F32 or C2T_BF16                                        */
   float beta;           /* 0 <= beta < 1                                              */
   int32_t entropy_top_m; /* 0: entropy over the full vocabulary (Eq. 2, line 1);
-                            M > 0: over the M most probable tokens (Eq. 2, line 2)    */
+                            M > 0: over the M most probable tokens, with the probabilities
+                            of the full softmax (Eq. 2, line 2).  Then a row is never split
+                            over workgroups: C2T_ERR_UNSUPPORTED if the vocabulary needs it */
 } c2t_config;
 
 /* Caller-owned [device] output buffers of c2t_finalize_tree, N = budget.
@@ -145,7 +147,8 @@ int c2t_finalize_tree(c2t_ctx* ctx, const c2t_tree_out* out, void* stream);
 int c2t_get_layer_rows(c2t_ctx* ctx, const int32_t** layer_rows);
 
 /* Launch-shape override for experiments: number of workgroups a logits row is split over
- * in the first layer (one row per sequence) and in later layers; 0 = library default. */
+ * in the first layer (one row per sequence) and in later layers; 0 = library default.
+ * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs, or above 1 with entropy_top_m > 0. */
 int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
 
 /* Optional timing of the logits-pass kernel with HIP events recorded on the caller's

@@ -6,7 +6,6 @@
 
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -29,8 +28,11 @@ constexpr int MAX_MAP_BYTES_BF16 = 16 * 1024;
 constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
 constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
 constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the workspace always has room for
-constexpr int TARGET_WORKGROUPS = 256;         // a split adds an epilogue and a merge: only split while the CUs are not all busy
-constexpr int MAX_DEFAULT_SPLITS = 8;
+// Row splits.  A split adds an epilogue, a device-scope ticket and a merge (a few microseconds of
+// dependent round trips), which costs more than it saves on the histogram path even for a single
+// sequence; the two-pass fp32 path is compute-heavy (an fp64 exp per element) and gains from a few.
+constexpr int TARGET_WORKGROUPS_F32 = 256;
+constexpr int MAX_DEFAULT_SPLITS_F32 = 4;
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -65,7 +67,7 @@ int check_config(const c2t_config* c) {
   if (c->top_k > C2T_MAX_TOP_K || c->max_frontier > C2T_MAX_FRONTIER || c->hidden > C2T_MAX_HIDDEN ||
       c->budget > C2T_MAX_BUDGET || (int64_t)c->max_frontier * c->top_k > C2T_MAX_CANDIDATES)
     return C2T_ERR_UNSUPPORTED;
-  if (c->entropy_top_m != 0) return C2T_ERR_UNSUPPORTED;
+  if (c->entropy_top_m != 0 && min_splits(*c) > 1) return C2T_ERR_UNSUPPORTED;   // the M largest logits of a row are found by one workgroup
   if ((int64_t)c->batch * c->max_frontier * min_splits(*c) > (1 << 24)) return C2T_ERR_UNSUPPORTED;
   return C2T_OK;
 }
@@ -119,8 +121,9 @@ namespace {
 // default number of workgroups a row is split over when `rows` rows are launched
 int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
   const int nmin = min_splits(c);
-  const int by_size = std::max(1, chunks_of(c) / (c.logits_dtype == C2T_BF16 ? HP_NT : NT_F32));   // at least one full sweep of the workgroup
-  const int64_t want = std::min<int64_t>((TARGET_WORKGROUPS + rows - 1) / rows, MAX_DEFAULT_SPLITS);
+  if (c.logits_dtype == C2T_BF16 || c.entropy_top_m > 0) return nmin;
+  const int by_size = std::max(1, chunks_of(c) / NT_F32);   // at least one full sweep of the workgroup
+  const int64_t want = std::min<int64_t>((TARGET_WORKGROUPS_F32 + rows - 1) / rows, MAX_DEFAULT_SPLITS_F32);
   const int64_t cap = L.partial_slots / rows;
   const int64_t ns = std::min<int64_t>(std::min<int64_t>(want, by_size), cap);
   return (int)std::max<int64_t>(ns, nmin);
@@ -131,11 +134,7 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   const c2t_config& c = x->cfg;
   const int cpc = cpc_of(c);
   const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
-  const char* ev = getenv("C2T_HIST_NT");
-  const int hist_nt = ev ? atoi(ev) : HP_NT;
-  const int cells = c.logits_dtype == C2T_BF16
-                        ? (hist_nt == 1024 ? cells_in_segment<1024, HP_CPC>(cps) : cells_in_segment<HP_NT, HP_CPC>(cps))
-                        : cps;
+  const int cells = c.logits_dtype == C2T_BF16 ? cells_in_segment<HP_NT, HP_CPC>(cps) : cps;
   const size_t map_lds = ((size_t)cells * keybytes_of(c) + 15) / 16 * 16;
   // element list of the selection: (2K-1) cells of cpc chunks, 8 bytes per element
   const size_t list_lds = (size_t)(2 * c.top_k - 1) * cpc * epc_of(c) * 8;
@@ -144,27 +143,24 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   ScoreParams sp;
   sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
   sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
-  sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta;
+  sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m;
   if (c.logits_dtype == C2T_BF16) {
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
     sp.lds_bytes = (int)lds;
-    if (hist_nt == 1024) {
-      static size_t lds_raised = 48 * 1024;   // dynamic LDS the runtime allows this kernel so far
-      if (lds > lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_raised = lds;
-      }
-      hipLaunchKernelGGL(k_logits_hist<1024>, dim3(grid), dim3(1024), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st.cls, x->st, sp);
-    } else {
-      static size_t lds_raised = 48 * 1024;
-      if (lds > lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_logits_hist<HP_NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_raised = lds;
-      }
-      hipLaunchKernelGGL(k_logits_hist<HP_NT>, dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e, x->st.cls, x->st, sp);
+    static size_t lds_raised[2] = {48 * 1024, 48 * 1024};   // dynamic LDS the runtime allows each kernel so far
+    const int topm = c.entropy_top_m > 0;
+    const void* fn = topm ? (const void*)k_logits_hist<HP_NT, true> : (const void*)k_logits_hist<HP_NT, false>;
+    if (lds > lds_raised[topm]) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      lds_raised[topm] = lds;
     }
+    if (topm)
+      hipLaunchKernelGGL((k_logits_hist<HP_NT, true>), dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
+                         x->st.cls, x->st, sp);
+    else
+      hipLaunchKernelGGL((k_logits_hist<HP_NT, false>), dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
+                         x->st.cls, x->st, sp);
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
     sp.lds_bytes = (int)lds;
@@ -325,6 +321,7 @@ int c2t_get_layer_rows(c2t_ctx* x, const int32_t** layer_rows) {
 int c2t_set_row_splits(c2t_ctx* x, int32_t first_layer, int32_t other_layers) {
   if (!x || first_layer < 0 || other_layers < 0) return C2T_ERR_INVALID_ARG;
   const c2t_config& c = x->cfg;
+  if (c.entropy_top_m > 0 && (first_layer > 1 || other_layers > 1)) return C2T_ERR_UNSUPPORTED;
   const int nmin = min_splits(c);
   const int nmax_size = std::max(1, chunks_of(c));
   int nf = first_layer ? first_layer : default_split(c, x->lay, c.batch);

@@ -279,9 +279,83 @@ __device__ __forceinline__ float block_max(float v, float* red /*[NT/WAVE]*/) {
 // ---------------------------------------------------------------------------------------
 // Generic path: two passes over the segment, fp64 exponentials.  Any dtype, any values.
 // ---------------------------------------------------------------------------------------
+// Sums of e^(x-m) and (x-m) e^(x-m) over the M largest logits of the segment (ties at the M-th
+// value: any of the equal logits, they contribute the same).  The M-th largest value is found
+// exactly by a radix select over the order-preserving 32-bit keys, 8 bits per pass over the segment
+// (an LDS histogram of the digit among the elements that match the prefix so far); one more pass
+// sums the terms above it.  out[0..1] in LDS, valid after the caller's next barrier.
+template <int DT, int NT>
+__device__ __forceinline__ void top_m_sums(const uint4* __restrict__ rowp, const Segment& sg, int M, float m,
+                                           double (*red)[NT / WAVE], double* out) {
+  typedef LogitTraits<DT> T;
+  __shared__ uint32_t dig[256];
+  __shared__ int32_t sh_digit, sh_above, sh_total;
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+  uint32_t prefix = 0, care = 0;
+  int remaining = M;
+  bool take_all = false;
+#pragma unroll 1
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 256; i += NT) dig[i] = 0u;
+    __syncthreads();
+    for (int g = sg.c0 + tid; g < sg.c1; g += NT) {
+      float x[T::EPC];
+      T::unpack(rowp[g], x);
+      const int nv = (g == sg.tail_chunk) ? sg.tail_valid : T::EPC;
+#pragma unroll
+      for (int j = 0; j < T::EPC; ++j) {
+        const uint32_t key = sortable_key(x[j]);
+        if (j < nv && (key & care) == prefix) atomicAdd(&dig[(key >> shift) & 255u], 1u);
+      }
+    }
+    __syncthreads();
+    if (tid < WAVE) {                                        // wave 0: lane l owns digits 255-4l .. 252-4l
+      uint32_t c[4]; int tot = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { c[j] = dig[255 - (4 * lane + j)]; tot += (int)c[j]; }
+      const int incl = wave_scan_incl(tot);
+      int run = incl - tot;                                  // elements with larger digits
+      if (run < remaining && incl >= remaining) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (run < remaining && run + (int)c[j] >= remaining) { sh_digit = 255 - (4 * lane + j); sh_above = run; }
+          run += (int)c[j];
+        }
+      }
+      if (lane == WAVE - 1) sh_total = incl;
+    }
+    __syncthreads();
+    if (sh_total < remaining) { take_all = true; break; }   // fewer matching elements than wanted: only in the first pass
+    remaining -= sh_above;
+    prefix |= (uint32_t)sh_digit << shift; care |= 255u << shift;
+    __syncthreads();
+  }
+  // prefix = key of the M-th largest logit; `remaining` (>= 1) of the logits equal to it are taken
+  double Z = 0.0, S = 0.0;
+  const double md = (double)m;
+  for (int g = sg.c0 + tid; g < sg.c1; g += NT) {
+    float x[T::EPC];
+    T::unpack(rowp[g], x);
+    const int nv = (g == sg.tail_chunk) ? sg.tail_valid : T::EPC;
+#pragma unroll
+    for (int j = 0; j < T::EPC; ++j) {
+      if (j < nv && x[j] > -INFINITY && (take_all || sortable_key(x[j]) > prefix)) {
+        const double t = (double)x[j] - md, e = exp(t);
+        Z += e;
+        if (e > 0.0) S += t * e;
+      }
+    }
+  }
+  if (!take_all && tid == 0) {
+    const float xt = key_to_float(prefix);
+    if (xt > -INFINITY) { const double t = (double)xt - md, e = exp(t); Z += remaining * e; if (e > 0.0) S += remaining * (t * e); }
+  }
+  block_sum2<NT>(Z, S, red, out);
+}
+
 // map_lds: one key per cell.
 template <int DT, int NT, int CPC>
-__device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, const Segment sg,
+__device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, int top_m, const Segment sg,
                                 unsigned char* map_lds, const SelectLds sel, RowResult* rr, uint32_t info_flags) {
   typedef LogitTraits<DT> T;
   typedef typename T::key_t key_t;
@@ -289,7 +363,7 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
   static_assert(CPC == 1 || CPC == 4, "a cell is one chunk or four sweeps of a lane");
   key_t* map = (key_t*)map_lds;
   const int ncells = cells_in_segment<NT, CPC>(sg.ncell);
-  __shared__ double red_d[2][NW], sum_d[2];
+  __shared__ double red_d[2][NW], sum_d[2], sum_m[2];
   __shared__ float red_f[NW];
   __shared__ uint32_t lane_keys[NT];
   __shared__ int32_t cell_list[SEL_CELL_CAP];
@@ -349,6 +423,12 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
     }
   }
   block_sum2<NT>(Z, S, red_d, sum_d);
+  if (top_m > 0) {
+    __syncthreads();
+    if (!seg_bad && m > -INFINITY) top_m_sums<DT, NT>(rowp, sg, top_m, m, red_d, sum_m);
+    else if (tid == 0) { sum_m[0] = 0.0; sum_m[1] = 0.0; }
+    __syncthreads();
+  }
 
   // tau = K-th largest of the lane maxima: a lower bound of the K-th largest logit
   if (wid == 0) {
@@ -400,6 +480,7 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
     RowPartial r;
     r.ref = (double)m; r.a = (double)m; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = seg_bad ? 0 : n_top; r.flags = (seg_bad ? 1u : 0u) | info_flags;
     rr->part = r;
+    if (top_m > 0) { rr->ZM = sum_m[0]; rr->SM = sum_m[1]; }
   }
 }
 
@@ -427,8 +508,8 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * (DT == 1 ? 2 : 4));
   const Segment sg = make_segment<T::EPC>(V, split, cps);
   __shared__ RowResult rr;
-  if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
-  else generic_segment<DT, NT, 1>(rowp, V, K, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
+  if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
+  else generic_segment<DT, NT, 1>(rowp, V, K, sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
   finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
 }
 
@@ -530,15 +611,17 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, int n_valid, Hist
 
 // One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
-template <int NT>
-__device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, const Segment& sg,
+// TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
+// default kernel carries none of its registers).
+template <int NT, bool TOPM>
+__device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
                                              unsigned char* map_lds, const SelectLds& sel, RowResult* rr) {
   constexpr int NW = NT / WAVE;
   constexpr int WPL = HP_WORDS / NT;                   // words per lane in the epilogue (8 at 512 threads)
   static_assert(NW <= 16 && WPL % 4 == 0, "one DPP row holds the per-wave partials; a lane reads whole 16-byte runs");
   uint16_t* map = (uint16_t*)map_lds;
-  __shared__ double red_d[2][NW], sum_d[2];
+  __shared__ double red_d[2][NW], sum_d[2], sum_m[2];
   __shared__ float red_v[NW];
   __shared__ uint32_t red_u[NW], red_m[NW];
   __shared__ int32_t sh_ntiny;
@@ -712,10 +795,53 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   // below the window exist and the K-th largest logit is not a positive window value (then they
   // could be among the top K, which the histogram cannot rank).
   const int n_elems = (sg.tail_chunk >= 0 ? (sg.ncell - 1) * 8 + sg.tail_valid : sg.ncell * 8);
-  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS)) {
+  // With the entropy over the M largest logits: also if logits below the window could be among them.
+  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS) ||
+      (TOPM && n_tiny > 0 && tot_p < M)) {
     __syncthreads();
-    generic_segment<1, NT, HP_CPC>(rowp, V, K, sg, map_lds, sel, rr, 2u);
+    generic_segment<1, NT, HP_CPC>(rowp, V, K, M, sg, map_lds, sel, rr, 2u);
     return;
+  }
+  if (TOPM) {
+    // Eq. 2, second line: Z and S restricted to the M largest logits.  A lane's values, from the
+    // top: its positive magnitudes descending, then its negative ones ascending; `above` of them
+    // lie in other lanes.  Same reference chain as for S (lane top, wave top, m): one sign throughout.
+    double zm = 0.0, sm = 0.0;
+    const int above_p = tot_p - (before_p + incl_p), above_n = tot_p + before_n + incl_n - lane_neg;
+    const double vt = (double)vtop;
+    if (lane_pos > 0 && above_p < M) {
+      const double* tp = tab_e + (HP_WORDS + WPL * tid);
+      int run = above_p;
+#pragma unroll
+      for (int j = WPL - 1; j >= 0; --j) {
+        const int n = (int)(cw[j] & 0xffffu), take = max(0, min(n, M - run));
+        run += n;
+        if (take) { const double t = (double)take * tp[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, false) - vt) * t; }
+      }
+    }
+    if (lane_neg > 0 && above_n < M) {
+      const double* tn = tab_e + (HP_WORDS - WPL * (tid + 1));
+      int run = above_n;
+#pragma unroll
+      for (int j = 0; j < WPL; ++j) {
+        const int n = (int)(cw[j] >> 16), take = max(0, min(n, M - run));
+        run += n;
+        if (take) { const double t = (double)take * tn[WPL - 1 - j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, true) - vt) * t; }
+      }
+    }
+    if (lane_pos | lane_neg) sm += (vt - (double)vw) * zm;
+    zm = wave_sum(zm); sm = wave_sum(sm);
+    if (lane == 0) { red_d[0][wid] = zm; red_d[1][wid] = sm; }     // red_v still holds the waves' top values
+    __syncthreads();
+    if (wid == 0) {
+      double tz = 0.0, ts = 0.0;
+      if (lane < NW && red_d[0][lane] > 0.0) { tz = red_d[0][lane]; ts = red_d[1][lane] + ((double)red_v[lane] - (double)m) * tz; }
+      tz += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR1, 0xf>(ts);
+      tz += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(ts);
+      tz += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(ts);
+      tz += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(ts);
+      if (lane == 0) { sum_m[0] = tz; sum_m[1] = ts; }
+    }
   }
   float tau = -INFINITY;
   int eq_limit = K;
@@ -754,13 +880,14 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     RowPartial r;
     r.ref = (double)m; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
     rr->part = r;
+    if (TOPM) { rr->ZM = sum_m[0]; rr->SM = sum_m[1]; }
   }
 }
 
 // grid: rows_launched * nsplit workgroups of NT threads.
 // Dynamic LDS (sp.lds_bytes): [HP_WORDS counters | cell map, padded to 16 bytes]; the selection's
 // element list and the tail reuse all of it.
-template <int NT>
+template <int NT, bool TOPM>
 __global__ __launch_bounds__(NT, 8) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
     const float* __restrict__ cls, TreeState st, ScoreParams sp) {
@@ -774,8 +901,8 @@ __global__ __launch_bounds__(NT, 8) void k_logits_hist(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
   const Segment sg = make_segment<8>(V, split, cps);
   __shared__ RowResult rr;
-  if (sg.ncell == 0) { if (threadIdx.x == 0) rr.part = empty_partial(); }
-  else hist_segment<NT>(rowp, V, K, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
+  if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
+  else hist_segment<NT, TOPM>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
   finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);
 }

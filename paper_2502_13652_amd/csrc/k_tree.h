@@ -66,6 +66,7 @@ constexpr int C2T_MAX_CANDIDATES_DEV = 2048;              // F*K limit of the pe
 struct ScoreParams {
   RowPartial* part; float* part_topv; int32_t* part_topi;    // [launched row][split] records and their top-K lists
   int nsplit, rows_per_seq, F, K, N, h, layer;
+  int M;                                                     // 0: entropy over the whole row; M > 0: over the M largest logits
   int lds_bytes;                                             // dynamic LDS of the launch
   float z_beta;
 };
@@ -74,6 +75,7 @@ struct ScoreParams {
 // segment's top-K list (value desc, id asc).
 struct RowResult {
   RowPartial part;
+  double ZM, SM;      // the sums of Z and S restricted to the M largest logits (Eq. 2, second line); M > 0 only
   float topv[64];
   int32_t topi[64];
 };
@@ -170,7 +172,9 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
   // H = -sum p ln p = ln Zr - Sr / Zr
   const double sc = rr.part.a == R ? 1.0 : exp(rr.part.a - R);
   const double Zr = Z * sc, Sr = rr.part.S * sc;
-  const float H = bad ? 0.f : (float)(log(Zr) - Sr / Zr);
+  // Eq. 2, second line: -sum over the M most probable tokens of p ln p, p from the full softmax:
+  // (ln Zr * ZMr - SMr) / Zr with the sums restricted to those tokens
+  const float H = bad ? 0.f : sp.M > 0 ? (float)((log(Zr) * (rr.ZM * sc) - rr.SM * sc) / Zr) : (float)(log(Zr) - Sr / Zr);
   float z = -INFINITY, p32 = 0.f, P32 = 0.f; int tok = -1;
   if (!bad && tid < rr.part.n_top) {
     tok = rr.topi[tid];

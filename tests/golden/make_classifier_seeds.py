@@ -6,7 +6,11 @@ seed s >= 0 for which the oracle, run on the first min(B, 4) sequences of worklo
   (a) lets between 20% and 80% of the second layer's candidates pass the threshold beta, and
   (b) builds, for every one of those sequences, a tree that uses the whole node budget or is still
       growing in the last layer (so the workload exercises every layer, not a tree that dies early).
-Usage: python tests/golden/make_classifier_seeds.py
+For the chain configuration (F = K = 1, Sec. 5.5) the trees are chains that are meant to stop early:
+there the rule is, on the first 64 sequences, (a) as above and (b') at least three distinct chain
+lengths whose mean lies between a quarter and three quarters of the maximum depth.
+Configurations already in the file keep their seed unless --all is given.
+Usage: python tests/golden/make_classifier_seeds.py [--all]
 """
 import json
 import os
@@ -42,20 +46,31 @@ def evaluate(cfg, seed, logits):
 
 
 def main():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "classifier_seeds.json")
     result = {}
+    if "--all" not in sys.argv and os.path.exists(path):
+        with open(path) as f:
+            result = json.load(f)
     for name, cfg in W.CONFIGS.items():
-        ns = min(cfg["B"], 4)
+        if name in result:
+            continue
+        chain = cfg["F"] == 1 and cfg["K"] == 1
+        ns = min(cfg["B"], 64 if chain else 4)
         logits = [W.as_numpy_bits(W.logits_layer(cfg, l, seqs=range(ns))) for l in range(cfg["D"])]
         for seed in range(2000):
             frac, nn, alive = evaluate(cfg, seed, logits)
-            ok = frac is not None and 0.2 <= frac <= 0.8 and all(n == cfg["N"] or a > 0 for n, a in zip(nn, alive))
-            print(name, seed, frac, nn, alive, "OK" if ok else "", flush=True)
+            if chain:
+                ok = (frac is not None and 0.2 <= frac <= 0.8 and len(set(nn)) >= 3
+                      and 0.25 * cfg["D"] <= float(np.mean(nn)) <= 0.75 * cfg["D"])
+            else:
+                ok = frac is not None and 0.2 <= frac <= 0.8 and all(n == cfg["N"] or a > 0 for n, a in zip(nn, alive))
+            print(name, seed, frac, nn if not chain else sorted(set(nn)), alive if not chain else "", "OK" if ok else "", flush=True)
             if ok:
                 result[name] = dict(seed=seed, layer1_pass_fraction=frac, n_nodes=nn)
                 break
         else:
             raise SystemExit("no seed found for " + name)
-    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "classifier_seeds.json"), "w") as f:
+    with open(path, "w") as f:
         json.dump(result, f, indent=1)
 
 

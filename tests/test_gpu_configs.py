@@ -19,7 +19,10 @@ def _layers(cfg, name, instance=0, keep=True):
         if l not in cache:
             if not keep:
                 cache.clear()
-            cache[l] = W.logits_layer(cfg, l, device="cuda", instance=instance)
+            # single sequences: the CPU generator's stream, on which the classifier seeds were chosen
+            # (torch's GPU generator gives other rows, and e.g. a cfg3 tree that dies at the root)
+            gen = "cpu" if cfg["B"] == 1 else "cuda"
+            cache[l] = W.logits_layer(cfg, l, device=gen, instance=instance).cuda()
         return cache[l]
     return get
 
@@ -53,6 +56,43 @@ def test_batched_configs_full_size_sampled_oracle(name, sample):
         assert (m.sum(axis=1)[:k] == go["position"][b, :k]).all()     # ancestors + self = depth + 1
         assert not m[k:].any()
     print(name, "nodes/seq mean %.1f" % n.mean(), "min margins", audit["min_thr_margin"].min(), audit["min_rank_gap"].min())
+
+
+@pytest.mark.parametrize("name,sample", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 6)])
+def test_entropy_over_top_1000_whole_trees(name, sample):
+    # the paper's own configuration of the H feature: Eq. 2, second line with M = 1000
+    cfg = dict(W.CONFIGS[name], entropy_top_m=1000)
+    rng = np.random.default_rng(3)
+    seqs = sorted(rng.choice(cfg["B"], sample, replace=False).tolist())
+    total = 0
+    # the stored seeds were chosen for the full-vocabulary entropy; with another H feature the same
+    # classifier may prune everything at the root, so a few neighbouring seeds are run as well
+    for ds in range(1 if cfg["B"] > 1 else 4):
+        cls = W.classifier(cfg, W.classifier_seed(name) + ds)
+        print("config", name, "top-1000 entropy, classifier seed +%d, oracle on sequences" % ds, seqs, flush=True)
+        go, oo, audit = run_both(cfg, cls, _layers(cfg, name, keep=cfg["B"] == 1), seqs=seqs, tag="%s M=1000 seed+%d" % (name, ds))
+        print(name, "M=1000 n_nodes", go["n_nodes"][seqs].tolist())
+        total += int(go["n_nodes"].sum())
+    assert total > 0
+
+
+def test_batched_chain_mode_ragged_lengths():
+    # Sec. 5.5: one child per node; the classifier is an early-exit rule and sequences stop at
+    # different depths.  Full batch on the GPU, the oracle replays a sample of the sequences.
+    cfg = W.CONFIGS["chain"]
+    cls = W.classifier(cfg, W.classifier_seed("chain"))
+    rng = np.random.default_rng(11)
+    seqs = sorted(rng.choice(cfg["B"], 24, replace=False).tolist())
+    print("config chain, oracle on sequences", seqs, flush=True)
+    go, oo, audit = run_both(cfg, cls, _layers(cfg, "chain"), seqs=seqs, tag="chain")
+    n = go["n_nodes"]
+    assert len(set(n.tolist())) >= 3, "the workload is meant to have ragged chain lengths"
+    for b in range(cfg["B"]):
+        k = int(n[b])
+        np.testing.assert_array_equal(go["parent"][b, :k], np.arange(k) - 1)          # a chain
+        np.testing.assert_array_equal(go["position"][b, :k], np.arange(k) + 1)
+        np.testing.assert_array_equal(go["mask"][b, :k, :k], np.tril(np.ones((k, k), np.uint8)))
+    print("chain lengths: mean %.2f, histogram" % n.mean(), np.bincount(n, minlength=cfg["D"] + 1).tolist())
 
 
 def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():

@@ -103,6 +103,42 @@ def test_rows_against_oracle(dtype, V, K, splits):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,M", [(32000, 1000), (128256, 1000), (5003, 1), (5003, 37), (5003, 5003), (70, 1000)])
+def test_entropy_over_the_top_m_against_oracle(dtype, V, M):
+    # Eq. 2, second line: H over the M most probable tokens of the full softmax
+    from oracle import ref_entropy_top_m, ref_row
+    from paper_2502_13652_amd import C2TContext
+    rng = np.random.default_rng(V * 7 + M)
+    names, rows = adversarial_rows(V, rng, dtype == "bf16")
+    B, K = rows.shape[0], 4
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = torch.from_numpy(rows).to(tdt).view(B, 1, V)
+    if V % 8:
+        xp = torch.full((B, 1, (V + 7) // 8 * 8), float("inf"), dtype=tdt); xp[:, :, :V] = x; x = xp
+    from paper_2502_13652_amd import C2TError
+    try:
+        ctx = C2TContext(B, V, 1, K, 1, 1, 2, 1 if dtype == "bf16" else 0, 0.0, entropy_top_m=M)
+    except C2TError as e:
+        assert e.code == -2 and dtype == "f32" and V > 49152      # an fp32 row this long needs splits
+        pytest.skip("top-M entropy needs unsplit rows; an fp32 row of this length must be split")
+    W1 = np.zeros((2, 3), np.float32); W1[0, 0] = 1
+    ctx.set_classifier(W1, np.zeros(2, np.float32), np.array([1, 0], np.float32), 0.0)
+    print("top-M entropy V=%d M=%d %s" % (V, M, dtype), flush=True)
+    ctx.reset()
+    ctx.expand_layer(x.cuda())
+    torch.cuda.synchronize()
+    c = to_np(ctx.candidates())
+    xin = x[:, 0, :V].contiguous()
+    bits = xin.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else xin.numpy()
+    for b, name in enumerate(names):
+        HM = ref_entropy_top_m(bits[b], M)
+        full = ref_row(bits[b], 1)["H"]
+        assert close(c["H"][b, 0], np.float32(HM), atol=V * 2.0 ** -53).all(), "%s H_M: %g vs %g (full %g)" % (name, c["H"][b, 0], HM, full)
+        if M >= V:
+            assert close(c["H"][b, 0], np.float32(full), atol=V * 2.0 ** -53).all(), name
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_bad_rows_set_status_and_yield_nothing(dtype):
     from paper_2502_13652_amd import C2TContext
     V, K = 4096 + 8, 4

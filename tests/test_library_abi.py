@@ -44,8 +44,10 @@ def test_config_validation(lib):
                 dict(top_k=5, vocab=4), dict(budget=0), dict(hidden=0)):
         assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**bad)), ctypes.byref(need)) == -1, bad
     for big in (dict(top_k=65, max_frontier=1), dict(max_frontier=65, top_k=1), dict(hidden=257), dict(budget=1025),
-                dict(max_frontier=64, top_k=64), dict(entropy_top_m=1000)):
+                dict(max_frontier=64, top_k=64), dict(entropy_top_m=1000, vocab=1 << 22)):
         assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**big)), ctypes.byref(need)) == -2, big
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=1000)), ctypes.byref(need)) == 0
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=-1)), ctypes.byref(need)) == -1
 
 
 def test_workspace_and_state_errors(lib):

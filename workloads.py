@@ -41,6 +41,11 @@ CONFIGS = {
     "cfg5": dict(idx=5, B=256, V=152064, dtype="bf16", D=10, F=32, K=32, h=64, beta=0.3, N=128,
                  zipf_s=1.0, sigma=(0.5, 8.0), spike_frac=0.05,
                  desc="large-vocabulary stress case, 256 sequences"),
+    # Sec. 5.5 (chain mode): one child per node, so the tree is a chain and the classifier is an
+    # early-exit rule; many sequences, ragged lengths.  Not one of the five benchmark configurations.
+    "chain": dict(idx=6, B=1024, V=32000, dtype="bf16", D=8, F=1, K=1, h=12, beta=0.5, N=8,
+                  zipf_s=1.1, sigma=(1.0, 6.0), spike_frac=0.0,
+                  desc="batched chain mode, 1024 sequences, one child per node"),
 }
 
 

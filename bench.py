@@ -27,6 +27,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (default: batched serving, B=64, V=128256)")
     ap.add_argument("--splits", default="", help="row splits 'first,other' (0 = default)")
+    ap.add_argument("--entropy-top-m", type=int, default=0,
+                    help="M > 0: entropy over the M most probable tokens (Eq. 2, second line) instead of the whole row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
@@ -50,7 +52,8 @@ def main():
     # chosen on (torch's CPU and GPU generators differ; a GPU-generated cfg3 tree dies at the root).
     gen = "cpu" if B * F * V * D * esz <= (256 << 20) else dev
     layers = [W.logits_layer(cfg, l, device=gen).to(dev) for l in range(D)]
-    ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"], device=dev)
+    ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"],
+                     entropy_top_m=a.entropy_top_m, device=dev)
     ctx.set_classifier(*cls)
     if a.splits:
         ctx.set_row_splits(*[int(x) for x in a.splits.split(",")])
@@ -109,7 +112,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
-                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "classifier_seed": W.classifier_seed(a.workload),
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
@@ -127,6 +130,8 @@ def main():
         nseq = a.cpu_seqs or max(1, min(B, int(1.0e9 / per_seq_elems)))
         sl = [W.as_numpy_bits(x[:nseq].cpu()) for x in layers]
         t = RefTree(nseq, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"])
+        if a.entropy_top_m:
+            t.set_entropy_top_m(a.entropy_top_m)
         t.set_classifier(*cls)
         t.reset()
         c0 = time.perf_counter()

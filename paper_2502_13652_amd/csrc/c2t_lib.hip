@@ -90,7 +90,7 @@ Layout make_layout(const c2t_config& c) {
   L.part = take((size_t)L.partial_slots * sizeof(RowPartial));
   L.part_topv = take((size_t)L.partial_slots * K * 4);
   L.part_topi = take((size_t)L.partial_slots * K * 4);
-  L.tab_e = take((size_t)HP_BINS * 8);
+  L.tab_e = take((size_t)HP_TAB_DOUBLES * 8);
   L.total = o;
   return L;
 }
@@ -237,7 +237,7 @@ int c2t_set_classifier(c2t_ctx* x, const float* W1, const float* b1, const float
     return C2T_ERR_HIP;
   // table of e^v for the bf16 value histogram (device-side fp64 exp), once per context
   if (!x->have_cls && x->cfg.logits_dtype == C2T_BF16) {
-    hipLaunchKernelGGL(k_init_exp_table, dim3(HP_BINS / 256), dim3(256), 0, (hipStream_t)stream, x->tab_e);
+    hipLaunchKernelGGL(k_init_exp_table, dim3((HP_TAB_DOUBLES + 255) / 256), dim3(256), 0, (hipStream_t)stream, x->tab_e);
     if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
   }
   x->have_cls = true;

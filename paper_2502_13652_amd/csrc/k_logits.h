@@ -534,17 +534,66 @@ __device__ __forceinline__ float hp_value_of_mag(uint32_t magidx, bool negative)
   return __uint_as_float(((HP_MAG_LO + magidx) << 16) | (negative ? 0x80000000u : 0u));
 }
 
-// e^v for every value of the window, fp64, in value order (index = rank), so that the ranks a
-// lane owns in the epilogue are two contiguous runs.  Filled once per context.
-__global__ void k_init_exp_table(double* __restrict__ tab_e) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r < HP_BINS) tab_e[r] = exp((double)__uint_as_float(hp_code_of_rank(r) << 16));
+// e^v for the window's values, factored so that the tables are small enough to stay in cache:
+// v = s 2^E (1 + f/128) with f = 16 fh + fl, so e^v = A[s][e][fh] * B[s][e][fl] with
+// A = exp(s 2^E (1 + fh/8)) and B = exp(s 2^E fl/128) (both arguments exact), e = exponent index
+// inside the window (0..31).  Layout: A+ [256] | A- [256] | B+ [512] | B- [512] doubles (12 KB; a
+// table of all 8192 values is 64 KB and was re-fetched from memory by nearly every workgroup).
+// The product of two correctly rounded factors is within 3e-16 of e^v.  Filled once per context.
+constexpr int HP_TAB_A = 256, HP_TAB_B = 512, HP_TAB_DOUBLES = 2 * HP_TAB_A + 2 * HP_TAB_B;
+__global__ void k_init_exp_table(double* __restrict__ tab) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= HP_TAB_DOUBLES) return;
+  const bool is_b = i >= 2 * HP_TAB_A;
+  const int k = is_b ? i - 2 * HP_TAB_A : i, half = is_b ? HP_TAB_B : HP_TAB_A;
+  const bool neg = k >= half;
+  const int kk = neg ? k - half : k;
+  const int e = is_b ? kk >> 4 : kk >> 3, frac = is_b ? kk & 15 : kk & 7;
+  const double p2 = ldexp(1.0, (int)(HP_MAG_LO >> 7) + e - 127);                 // 2^E
+  const double arg = is_b ? p2 * (double)frac / 128.0 : p2 * (1.0 + (double)frac / 8.0);
+  tab[i] = exp(neg ? -arg : arg);
+}
+// The lane that owns magnitude indices 8t .. 8t+7 (one exponent, fh fixed): e^(+|v_j|) and e^(-|v_j|)
+template <int WPL>
+__device__ __forceinline__ void load_exp_factors(const double* __restrict__ tab, int tid, double (&evp)[WPL], double (&evn)[WPL]) {
+  const int mag0 = WPL * tid, e = mag0 >> 7, f0 = mag0 & 127;
+  const double ap = tab[e * 8 + (f0 >> 4)], an = tab[HP_TAB_A + e * 8 + (f0 >> 4)];
+  const double* bp = tab + 2 * HP_TAB_A + e * 16 + (f0 & 15);
+  const double* bn = bp + HP_TAB_B;
+#pragma unroll
+  for (int j = 0; j < WPL; ++j) { evp[j] = ap * bp[j]; evn[j] = an * bn[j]; }
 }
 
 typedef _Float16 c2t_half2 __attribute__((ext_vector_type(2)));
 typedef unsigned short c2t_ushort2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(c2t_half2, a), __builtin_bit_cast(c2t_half2, b)));
+}
+// The same instruction without the canonicalising copies the builtin adds in front of it (an
+// instruction per operand): for the streaming loop, whose patterns are never signalling NaNs that matter.
+__device__ __forceinline__ uint32_t pk_max_f16_raw(uint32_t a, uint32_t b) {
+  uint32_t d;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+  return d;
+}
+// per 16-bit half: a * b + c (mod 2^16)
+__device__ __forceinline__ uint32_t pk_mad_u16(uint32_t a, uint32_t b_sgpr, uint32_t c) {
+  uint32_t d;
+  asm("v_pk_mad_u16 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(b_sgpr), "v"(c));
+  return d;
+}
+// bits 16..27 of w: the histogram word of the upper bf16 (written out because the compiler turns the
+// bit-field extract into shift, mask and a separate add of the array base: one instruction more)
+__device__ __forceinline__ uint32_t bits_16_27(uint32_t w) {
+  uint32_t d;
+  asm("v_bfe_u32 %0, %1, 16, 12" : "=v"(d) : "v"(w));
+  return d;
+}
+// mask ? 65536 : 1 for mask = 0 or ~0: the histogram increment of a negative / positive value
+__device__ __forceinline__ uint32_t hist_increment(int32_t sign_mask, uint32_t c65536_sgpr) {
+  uint32_t d;
+  asm("v_bfi_b32 %0, %1, %2, 1" : "=v"(d) : "v"(sign_mask), "s"(c65536_sgpr));
+  return d;
 }
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(c2t_ushort2, a), __builtin_bit_cast(c2t_ushort2, b)));
@@ -578,34 +627,30 @@ __device__ __forceinline__ uint32_t hist_elements(const uint4& q, int n_valid, H
   return c16 | (c16 << 16);
 }
 
-// Counts the chunk's values; returns the chunk maximum as a packed pattern (both halves <= max,
-// one of them equal to it).
-__device__ __forceinline__ uint32_t hist_chunk(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
+// Counts the values of a whole chunk; returns the chunk maximum as a packed pattern (both halves
+// <= max, one of them equal to it).
+__device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint32_t* __restrict__ hist) {
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-  // |code| range of the chunk; NaN and infinities have the largest magnitudes
-  uint32_t mx = a.mag_max, mn = 0x7fff7fffu;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t mag = w[j] & 0x7fff7fffu;
-    mx = pk_max_u16(mx, mag); mn = pk_min_u16(mn, mag);
-  }
-  constexpr uint32_t LO2 = HP_MAG_LO | (HP_MAG_LO << 16);
+  // Per half d = 2 |code| - 2 LO (mod 2^16), with the sign shifted out by the doubling: the value
+  // lies in the window iff d < 2 SPAN = 8192, i.e. iff bits 13..15 of d are clear.
+  constexpr uint32_t TWO2 = 0x00020002u, BIAS2 = ((0x10000u - 2u * HP_MAG_LO) & 0xffffu) * 0x00010001u;
+  static_assert(2 * HP_MAG_SPAN == 8192 && HP_WORDS == 4096, "window test and 12-bit word index below");
+  const uint32_t dm = pk_max_u16(pk_max_u16(pk_mad_u16(w[0], TWO2, BIAS2), pk_mad_u16(w[1], TWO2, BIAS2)),
+                                 pk_max_u16(pk_mad_u16(w[2], TWO2, BIAS2), pk_mad_u16(w[3], TWO2, BIAS2)));
   uint32_t pat;
-  if (pk_min_u16(mn, LO2) != LO2 || n_valid != 8) {          // rare: a logit below the window, or the row's last chunk
-    pat = hist_elements(q, n_valid, a, hist);
+  if (dm & 0xE000E000u) {                                     // rare: a logit outside the window
+    pat = hist_elements(q, 8, a, hist);
   } else {
-    a.mag_max = mx;
-    // inside the window bf16 bit patterns order exactly like fp16 bit patterns (above it the
-    // row leaves this path anyway)
-    pat = pk_max_f16(pk_max_f16(w[0], w[1]), pk_max_f16(w[2], w[3]));
+    // inside the window bf16 bit patterns order exactly like fp16 bit patterns
+    pat = pk_max_f16_raw(pk_max_f16_raw(w[0], w[1]), pk_max_f16_raw(w[2], w[3]));
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       // +1 into the low half for a positive value, into the high half for a negative one
-      atomicAdd(&hist[(w[j] >> 16) & (HP_WORDS - 1)], __umul24(w[j] >> 31, 0xffffu) + 1u);
-      atomicAdd(&hist[w[j] & (HP_WORDS - 1)], __umul24((w[j] >> 15) & 1u, 0xffffu) + 1u);
+      atomicAdd(&hist[bits_16_27(w[j])], hist_increment((int32_t)w[j] >> 31, 0x10000u));
+      atomicAdd(&hist[w[j] & (HP_WORDS - 1)], hist_increment(__builtin_amdgcn_sbfe((int32_t)w[j], 15, 1), 0x10000u));
     }
   }
-  a.M2 = pk_max_f16(a.M2, pat);
+  a.M2 = pk_max_f16_raw(a.M2, pat);
   return pat;
 }
 
@@ -644,29 +689,34 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     // in their epilogues still covers the HBM latency.  Unrolled by four so that each buffer is
     // refilled right after it has been counted, without register copies.
     int g = sg.c0 + tid;
-    const int c1 = sg.c1, tail = sg.tail_chunk, tv = sg.tail_valid;
+    const int c1 = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;   // whole chunks; a partial last chunk is counted below
     const uint4* dummy = rowp + sg.c0;                   // in-bounds address for lanes past their last chunk
 #define C2T_LOAD(i) load_stream((i) < c1 ? rowp + (i) : dummy)
-#define C2T_COUNT(q, i) hist_chunk(q, (i) == tail ? tv : 8, a, hist)
+#define C2T_COUNT(q, i) hist_chunk(q, a, hist)
     uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + NT), qc = C2T_LOAD(g + 2 * NT), qd = C2T_LOAD(g + 3 * NT);
     uint16_t* mp = map + tid;
     // groups of four sweeps in which every lane has a chunk
     for (int it = (c1 - sg.c0) / (4 * NT); it > 0; --it, g += 4 * NT, mp += NT) {
       uint32_t key = C2T_COUNT(qa, g);
       qa = C2T_LOAD(g + 4 * NT);
-      key = pk_max_f16(key, C2T_COUNT(qb, g + NT));
+      key = pk_max_f16_raw(key, C2T_COUNT(qb, g + NT));
       qb = C2T_LOAD(g + 5 * NT);
-      key = pk_max_f16(key, C2T_COUNT(qc, g + 2 * NT));
+      key = pk_max_f16_raw(key, C2T_COUNT(qc, g + 2 * NT));
       qc = C2T_LOAD(g + 6 * NT);
-      key = pk_max_f16(key, C2T_COUNT(qd, g + 3 * NT));
+      key = pk_max_f16_raw(key, C2T_COUNT(qd, g + 3 * NT));
       qd = C2T_LOAD(g + 7 * NT);
-      *mp = (uint16_t)pk_max_f16(key, key >> 16);
+      *mp = (uint16_t)pk_max_f16_raw(key, key >> 16);
     }
-    if (g < c1) {                                        // the last, partial group: up to four chunks of this lane
-      uint32_t key = C2T_COUNT(qa, g);
-      if (g + NT < c1) key = pk_max_f16(key, C2T_COUNT(qb, g + NT));
-      if (g + 2 * NT < c1) key = pk_max_f16(key, C2T_COUNT(qc, g + 2 * NT));
-      if (g + 3 * NT < c1) key = pk_max_f16(key, C2T_COUNT(qd, g + 3 * NT));
+    // the last, partial group: up to four chunks of this lane, the row's partial last chunk among them
+    const int tail = sg.tail_chunk;
+    if (g < c1 || g == tail) {
+      uint32_t key = g < c1 ? C2T_COUNT(qa, g) : hist_elements(rowp[tail], sg.tail_valid, a, hist);
+      if (g + NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qb, g + NT));
+      else if (g + NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
+      if (g + 2 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qc, g + 2 * NT));
+      else if (g + 2 * NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
+      if (g + 3 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qd, g + 3 * NT));
+      else if (g + 3 * NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
       *mp = (uint16_t)pk_max_f16(key, key >> 16);
     }
 #undef C2T_COUNT
@@ -674,16 +724,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   }
   if (a.n_tiny) { atomicAdd(&sh_ntiny, a.n_tiny); atomicAdd(&sh_stiny, a.s_tiny); }
 
-  // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  Its slices of
-  // the e^v table (ranks 4096 + i for +|v|, 4095 - i for -|v|) are issued now so that their latency
-  // hides behind the barrier.
+  // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  The table
+  // loads for their e^v are issued now so that their latency hides behind the barrier.
+  static_assert(WPL <= 8 && 16 % WPL == 0, "a lane's magnitudes share one exponent and one upper fraction");
   double evp[WPL], evn[WPL];
-  {
-    const double* tp = tab_e + (HP_WORDS + WPL * tid);
-    const double* tn = tab_e + (HP_WORDS - WPL * (tid + 1));
-#pragma unroll
-    for (int j = 0; j < WPL; ++j) { evp[j] = tp[j]; evn[j] = tn[WPL - 1 - j]; }
-  }
+  load_exp_factors<WPL>(tab_e, tid, evp, evn);
   // per-wave: magnitude range and maximum
   {
     const uint32_t mx = wave_reduce_u32(a.mag_max, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
@@ -809,24 +854,26 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     double zm = 0.0, sm = 0.0;
     const int above_p = tot_p - (before_p + incl_p), above_n = tot_p + before_n + incl_n - lane_neg;
     const double vt = (double)vtop;
-    if (lane_pos > 0 && above_p < M) {
-      const double* tp = tab_e + (HP_WORDS + WPL * tid);
-      int run = above_p;
+    if ((lane_pos > 0 && above_p < M) || (lane_neg > 0 && above_n < M)) {
+      double ep[WPL], en[WPL];
+      load_exp_factors<WPL>(tab_e, tid, ep, en);
+      if (lane_pos > 0 && above_p < M) {
+        int run = above_p;
 #pragma unroll
-      for (int j = WPL - 1; j >= 0; --j) {
-        const int n = (int)(cw[j] & 0xffffu), take = max(0, min(n, M - run));
-        run += n;
-        if (take) { const double t = (double)take * tp[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, false) - vt) * t; }
+        for (int j = WPL - 1; j >= 0; --j) {
+          const int n = (int)(cw[j] & 0xffffu), take = max(0, min(n, M - run));
+          run += n;
+          if (take) { const double t = (double)take * ep[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, false) - vt) * t; }
+        }
       }
-    }
-    if (lane_neg > 0 && above_n < M) {
-      const double* tn = tab_e + (HP_WORDS - WPL * (tid + 1));
-      int run = above_n;
+      if (lane_neg > 0 && above_n < M) {
+        int run = above_n;
 #pragma unroll
-      for (int j = 0; j < WPL; ++j) {
-        const int n = (int)(cw[j] >> 16), take = max(0, min(n, M - run));
-        run += n;
-        if (take) { const double t = (double)take * tn[WPL - 1 - j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, true) - vt) * t; }
+        for (int j = 0; j < WPL; ++j) {
+          const int n = (int)(cw[j] >> 16), take = max(0, min(n, M - run));
+          run += n;
+          if (take) { const double t = (double)take * en[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, true) - vt) * t; }
+        }
       }
     }
     if (lane_pos | lane_neg) sm += (vt - (double)vw) * zm;

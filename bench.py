@@ -102,6 +102,17 @@ def main():
     stream_gbps = 5 * big.numel() / (e0.elapsed_time(e1) / 1e3) / 1e9
     del big
 
+    # HBM traffic per launch from the committed counter pass (rocprofv3 --pmc FETCH_SIZE, scaled by the
+    # factor the same counter shows for the plain read kernel); only for the workload it was taken on
+    traffic = None
+    if a.workload == "cfg4" and not a.splits and not a.entropy_top_m:
+        try:
+            import re
+            with open(os.path.join(ROOT, "profiles", "k_logits_hist_cfg4_pmc.md")) as f:
+                traffic = float(re.search(r"traffic_bytes_per_launch = (\d+)", f.read()).group(1))
+        except (OSError, AttributeError):
+            traffic = None
+
     n_nodes = out["n_nodes"].cpu().numpy()
     rec = {
         "metric": "draft-tree nodes scored/sec + logits-pass HBM GB/s (fraction of peak), 1 GPU",
@@ -115,7 +126,7 @@ def main():
                    "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "k_logits_hist<512>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>", "launches": int(a.steps * D),
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),

@@ -151,10 +151,10 @@ int c2t_get_layer_rows(c2t_ctx* ctx, const int32_t** layer_rows);
  * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs, or above 1 with entropy_top_m > 0. */
 int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
 
-/* Optional timing of the logits-pass kernel with HIP events recorded on the caller's
- * stream around each launch.  c2t_profile_enable creates `capacity` event pairs (host
- * resources; 0 disables and destroys them).  After the caller has synchronised the stream,
- * c2t_profile_read writes the duration in milliseconds of each launch recorded since the
+/* Optional timing of the layer kernel with HIP events attached to each launch on the caller's
+ * stream (they take the kernel's own begin and end).  c2t_profile_enable creates `capacity` event
+ * pairs (host resources; 0 disables and destroys them).  After the caller has synchronised the
+ * stream, c2t_profile_read writes the duration in milliseconds of each launch recorded since the
  * last read to ms[0..*n) ([host], capacity given in *n on entry) and forgets them. */
 int c2t_profile_enable(c2t_ctx* ctx, int32_t capacity);
 int c2t_profile_read(c2t_ctx* ctx, float* ms, int32_t* n);

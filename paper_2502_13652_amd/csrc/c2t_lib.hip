@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/c2t.h"
+#include <hip/hip_ext.h>
 #include "k_logits.h"
 #include "k_tree.h"
 
@@ -129,8 +130,10 @@ int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
   return (int)std::max<int64_t>(ns, nmin);
 }
 
+// ev0/ev1: optional events attached to the dispatch itself (they take the kernel's own begin and
+// end times, without the launch gap that events recorded around a launch include).
 hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit,
-                         hipStream_t s) {
+                         hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const c2t_config& c = x->cfg;
   const int cpc = cpc_of(c);
   const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
@@ -156,16 +159,16 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
       lds_raised[topm] = lds;
     }
     if (topm)
-      hipLaunchKernelGGL((k_logits_hist<HP_NT, true>), dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
-                         x->st.cls, x->st, sp);
+      hipExtLaunchKernelGGL((k_logits_hist<HP_NT, true>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride,
+                            c.vocab, cps, (const double*)x->tab_e, (const float*)x->st.cls, x->st, sp);
     else
-      hipLaunchKernelGGL((k_logits_hist<HP_NT, false>), dim3(grid), dim3(HP_NT), lds, s, logits, stride, c.vocab, cps, x->tab_e,
-                         x->st.cls, x->st, sp);
+      hipExtLaunchKernelGGL((k_logits_hist<HP_NT, false>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride,
+                            c.vocab, cps, (const double*)x->tab_e, (const float*)x->st.cls, x->st, sp);
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
     sp.lds_bytes = (int)lds;
-    hipLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, logits, stride, c.vocab,
-                       cps, x->st.cls, x->st, sp);
+    hipExtLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, ev0, ev1, 0, logits, stride,
+                          c.vocab, cps, (const float*)x->st.cls, x->st, sp);
   }
   return hipGetLastError();
 }
@@ -267,13 +270,10 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
   const int rows_per_seq = first ? 1 : c.max_frontier;
   const int nsplit = first ? x->ns_first : x->ns_other;
   const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size();
-  if (timed && hipEventRecord(x->ev[x->ev_used], s) != hipSuccess) return C2T_ERR_HIP;
-  hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, s);
+  hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, s,
+                               timed ? x->ev[x->ev_used] : nullptr, timed ? x->ev[x->ev_used + 1] : nullptr);
   if (e != hipSuccess) return C2T_ERR_HIP;
-  if (timed) {
-    if (hipEventRecord(x->ev[x->ev_used + 1], s) != hipSuccess) return C2T_ERR_HIP;
-    x->ev_used += 2;
-  }
+  if (timed) x->ev_used += 2;
   x->layer += 1;
   return C2T_OK;
 }

@@ -128,7 +128,17 @@ struct Cand {
   int32_t kept;      // 0 dropped, 1 kept
 };
 
+// Every candidate that was given a confidence, in the order it was scored (layer by layer, within a
+// layer by frontier slot, then by rank in the row); s = smallest classifier logit on the path from
+// the root's child down to the candidate (itself included).
+struct HistCand {
+  int32_t token, parent, depth;   // parent = index into the history, -1 for a child of the root
+  float P, H, z, s;
+};
+
 struct Seq {
+  std::vector<HistCand> hist;
+  std::vector<int32_t> node_hist;       // history index of each tree node
   std::vector<Node> nodes;
   std::vector<int32_t> frontier;        // node indices; -1 = root
   std::vector<int32_t> frontier_slot;   // slot of each frontier node's parent in the previous frontier
@@ -151,6 +161,8 @@ struct Tree {
 };
 
 void reset_seq(Seq& s) {
+  s.hist.clear();
+  s.node_hist.clear();
   s.nodes.clear();
   s.frontier.assign(1, -1);
   s.frontier_slot.assign(1, 0);
@@ -188,6 +200,15 @@ void expand_seq(Tree& t, Seq& s, const char* logits_seq, int64_t row_stride_elem
     }
   }
   s.scored += (int64_t)cand.size();
+  const int32_t hist_base = (int32_t)s.hist.size();
+  for (const Cand& q : cand) {
+    HistCand hc;
+    const int32_t parent_node = s.frontier[q.slot];
+    hc.token = q.token; hc.depth = t.layer; hc.P = q.P; hc.H = q.H; hc.z = q.z;
+    hc.parent = parent_node < 0 ? -1 : s.node_hist[parent_node];
+    hc.s = hc.parent < 0 ? q.z : std::min(s.hist[hc.parent].s, q.z);
+    s.hist.push_back(hc);
+  }
   // first pruning: keep iff C > beta  <=>  z > logit(beta)
   std::vector<int> surv;
   for (int i = 0; i < (int)cand.size(); ++i) {
@@ -224,6 +245,7 @@ void expand_seq(Tree& t, Seq& s, const char* logits_seq, int64_t row_stride_elem
     new_frontier.push_back((int32_t)s.nodes.size());
     new_slot.push_back(q.slot);
     s.nodes.push_back(n);
+    s.node_hist.push_back(hist_base + surv[i]);
   }
   s.frontier.swap(new_frontier);
   s.frontier_slot.swap(new_slot);
@@ -393,6 +415,50 @@ void c2t_ref_finalize(void* tp, int32_t* tokens, int32_t* parent, int32_t* posit
       } else {
         tokens[o] = -1; parent[o] = -1; position[o] = 0;
         conf[o] = 0; joint_prob[o] = 0; entropy[o] = 0;
+      }
+    }
+  }
+}
+
+// EAGLE-2-style reranking (Sec. 2.2: "reranks all candidate nodes, selecting the top N"): over every
+// candidate scored in any layer, kept by the prunings or not, the n_out best by s, the smallest
+// classifier logit on the candidate's path.  s never increases along a path, so with the order
+// (s desc, depth asc, scoring order asc) every selected candidate's parent is selected before it:
+// the result is a tree for any classifier, and for a classifier that is monotone along paths
+// (EAGLE-2's value = joint probability) it is the plain top-n_out by confidence.
+// Outputs as c2t_ref_finalize with N replaced by n_out; nodes in selection order.
+void c2t_ref_finalize_rerank(void* tp, int n_out, int32_t* tokens, int32_t* parent, int32_t* position, float* conf,
+                             float* joint_prob, float* entropy, float* path_min_z, int32_t* n_nodes, uint8_t* mask,
+                             uint32_t* status) {
+  Tree* t = (Tree*)tp;
+  const int N = n_out;
+  for (int b = 0; b < t->B; ++b) {
+    Seq& s = t->seq[b];
+    std::vector<int32_t> order(s.hist.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+      if (s.hist[x].s != s.hist[y].s) return s.hist[x].s > s.hist[y].s;
+      if (s.hist[x].depth != s.hist[y].depth) return s.hist[x].depth < s.hist[y].depth;
+      return x < y;
+    });
+    const int n = std::min(N, (int)order.size());
+    std::vector<int32_t> out_pos(s.hist.size(), -1);
+    for (int i = 0; i < n; ++i) out_pos[order[i]] = i;
+    n_nodes[b] = n;
+    status[b] = s.status;
+    uint8_t* mk = mask + (int64_t)b * N * N;
+    std::memset(mk, 0, (size_t)N * N);
+    for (int i = 0; i < N; ++i) {
+      int64_t o = (int64_t)b * N + i;
+      if (i < n) {
+        const HistCand& c = s.hist[order[i]];
+        tokens[o] = c.token; parent[o] = c.parent < 0 ? -1 : out_pos[c.parent]; position[o] = c.depth + 1;
+        conf[o] = (float)(1.0 / (1.0 + std::exp(-(double)c.z)));
+        joint_prob[o] = c.P; entropy[o] = c.H; path_min_z[o] = c.s;
+        for (int32_t j = order[i]; j >= 0; j = s.hist[j].parent) mk[(int64_t)i * N + out_pos[j]] = 1;
+      } else {
+        tokens[o] = -1; parent[o] = -1; position[o] = 0;
+        conf[o] = 0; joint_prob[o] = 0; entropy[o] = 0; path_min_z[o] = 0;
       }
     }
   }

@@ -61,6 +61,7 @@ def _load():
         L.c2t_ref_get_candidates.argtypes = [vp] * 9
         L.c2t_ref_get_audit.argtypes = [vp] * 4
         L.c2t_ref_finalize.argtypes = [vp] * 10
+        L.c2t_ref_finalize_rerank.argtypes = [vp, i32] + [vp] * 10
         L.c2t_ref_get_node_extras.argtypes = [vp] * 3
         _lib = L
         return L
@@ -215,4 +216,18 @@ class RefTree:
         self.L.c2t_ref_get_node_extras(self.h_, _ptr(p), _ptr(z))
         out["p"] = p
         out["z"] = z
+        return out
+
+    def finalize_rerank(self, n_out):
+        """Global top-n_out over every scored candidate by the path minimum of the classifier logit."""
+        B, N = self.B, int(n_out)
+        out = dict(tokens=np.zeros((B, N), np.int32), parent=np.zeros((B, N), np.int32),
+                   position=np.zeros((B, N), np.int32), conf=np.zeros((B, N), np.float32),
+                   joint_prob=np.zeros((B, N), np.float32), entropy=np.zeros((B, N), np.float32),
+                   path_min_z=np.zeros((B, N), np.float32),
+                   n_nodes=np.zeros(B, np.int32), mask=np.zeros((B, N, N), np.uint8),
+                   status=np.zeros(B, np.uint32))
+        self.L.c2t_ref_finalize_rerank(self.h_, N, *[_ptr(out[k]) for k in
+                                       ("tokens", "parent", "position", "conf", "joint_prob", "entropy", "path_min_z",
+                                        "n_nodes", "mask", "status")])
         return out

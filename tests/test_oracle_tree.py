@@ -120,6 +120,81 @@ def test_identity_classifier_reproduces_eagle2_expansion():
             assert out["joint_prob"][0, i] <= out["joint_prob"][0, par]
 
 
+def test_rerank_with_identity_classifier_is_eagle2_top_n():
+    # Sec. 2.2, reranking phase: with value = joint probability, all candidate nodes of the
+    # expansion are reranked and the top N selected; the joint probability never grows along a path,
+    # so the selection is a tree.  Independent construction: scipy softmax, plain sort.
+    rng = np.random.default_rng(23)
+    V, F, K, D, h = 200, 3, 3, 4, 2
+    logits = random_logits(rng, D, F, V)
+    t = RefTree(1, V, F, K, D, 100, h, 0, 0.0)
+    t.set_classifier(*identity_on_P(h))
+    run(t, logits)
+    frontier = [(1.0, -1)]
+    cands = []                        # every generated token: (P, depth, order, token, parent cand index)
+    for l in range(D):
+        children = []
+        for slot, (Pp, par) in enumerate(frontier):
+            p = softmax(logits[l][0][slot].astype(np.float64))
+            for tok in np.lexsort((np.arange(V), -logits[l][0][slot]))[:K]:
+                children.append((f32(f32(Pp) * f32(p[tok])), int(tok), slot, par))
+        base = len(cands)
+        for i, c in enumerate(children):
+            cands.append((c[0], l, base + i, c[1], c[3]))
+        ranked = sorted(range(len(children)), key=lambda i: (-float(children[i][0]), children[i][1], children[i][2]))
+        frontier = [(children[i][0], base + i) for i in ranked[:F]]
+    assert len(cands) == K + (D - 1) * F * K
+    for n_out in (1, 5, 12, len(cands), len(cands) + 7):
+        out = t.finalize_rerank(n_out)
+        want = sorted(cands, key=lambda c: (-float(c[0]), c[1], c[2]))[:n_out]
+        n = int(out["n_nodes"][0])
+        assert n == len(want)
+        np.testing.assert_array_equal(out["tokens"][0, :n], [c[3] for c in want])
+        np.testing.assert_array_equal(out["joint_prob"][0, :n], np.array([c[0] for c in want], f32))
+        np.testing.assert_array_equal(out["position"][0, :n], [c[1] + 1 for c in want])
+        pos = {c[2]: i for i, c in enumerate(want)}
+        np.testing.assert_array_equal(out["parent"][0, :n], [-1 if c[4] < 0 else pos[c[4]] for c in want])
+        assert not out["mask"][0, n:].any() and (out["tokens"][0, n:] == -1).all()
+
+
+def test_rerank_selection_is_a_tree_for_any_classifier():
+    # a classifier that is not monotone along paths: ranking by the path minimum of z keeps the
+    # selection closed under "parent of"; brute force over the recorded forest
+    rng = np.random.default_rng(24)
+    V, F, K, D, h = 64, 4, 3, 5, 6
+    for trial in range(6):
+        logits = random_logits(rng, D, F, V)
+        cls = ((0.8 * rng.standard_normal((h, 3))).astype(f32), (0.5 * rng.standard_normal(h)).astype(f32),
+               (0.8 * rng.standard_normal(h)).astype(f32), f32(0.2))
+        t = RefTree(1, V, F, K, D, 100, h, 0, 0.3)
+        t.set_classifier(*cls)
+        run(t, logits)
+        total = int(t.audit()["scored"][0])
+        everything = t.finalize_rerank(total + 3)
+        assert int(everything["n_nodes"][0]) == total
+        for n_out in (1, 7, total // 2, total):
+            out = t.finalize_rerank(n_out)
+            n = int(out["n_nodes"][0])
+            assert n == min(n_out, total)
+            par, s, z = out["parent"][0, :n], out["path_min_z"][0, :n], everything
+            assert (par < np.arange(n)).all()                                     # parents come first
+            assert (np.diff(s) <= 0).all()                                        # best path minimum first
+            for i in range(n):
+                zi = -np.log(1.0 / np.float64(out["conf"][0, i]) - 1.0)           # conf = sigmoid(z)
+                want = zi if par[i] < 0 else min(s[par[i]], zi)
+                assert abs(s[i] - want) <= 1e-5 * max(1.0, abs(want))            # s = min over the path
+                anc = {i}; j = i
+                while par[j] >= 0:
+                    j = par[j]; anc.add(j)
+                assert set(np.nonzero(out["mask"][0, i])[0].tolist()) == anc
+                assert out["position"][0, i] == len(anc)
+            # nothing left out beats something selected
+            if n < total:
+                assert everything["path_min_z"][0, n:total].max() <= s.min()
+            # a prefix of the full ranking
+            np.testing.assert_array_equal(out["tokens"][0, :n], everything["tokens"][0, :n])
+
+
 def test_candidate_count_matches_paper_tree_size():
     # Appendix B.1: K = 10, d_max = 11 gives complete trees of 1011 nodes = root + K + (d_max-1)*K*K
     g = GOLD["training_tree"]

@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--splits", default="", help="row splits 'first,other' (0 = default)")
     ap.add_argument("--entropy-top-m", type=int, default=0,
                     help="M > 0: entropy over the M most probable tokens (Eq. 2, second line) instead of the whole row")
+    ap.add_argument("--rerank", type=int, default=0,
+                    help="n > 0: finish with the EAGLE-2-style reranking of all scored candidates (Sec. 2.2), n nodes out")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
@@ -53,17 +55,20 @@ def main():
     gen = "cpu" if B * F * V * D * esz <= (256 << 20) else dev
     layers = [W.logits_layer(cfg, l, device=gen).to(dev) for l in range(D)]
     ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"],
-                     entropy_top_m=a.entropy_top_m, device=dev)
+                     entropy_top_m=a.entropy_top_m, rerank=1 if a.rerank else 0, device=dev)
     ctx.set_classifier(*cls)
     if a.splits:
         ctx.set_row_splits(*[int(x) for x in a.splits.split(",")])
-    out = ctx.new_tree_out()
+    out = ctx.new_tree_out(a.rerank or None)
 
     def step():
         ctx.reset()
         for l in range(D):
             ctx.expand_layer(layers[l])
-        ctx.finalize_tree(out)
+        if a.rerank:
+            ctx.finalize_tree_reranked(a.rerank, out)
+        else:
+            ctx.finalize_tree(out)
 
     for _ in range(a.warmup):
         step()
@@ -105,7 +110,7 @@ def main():
     # HBM traffic per launch from the committed counter pass (rocprofv3 --pmc FETCH_SIZE, scaled by the
     # factor the same counter shows for the plain read kernel); only for the workload it was taken on
     traffic = None
-    if a.workload == "cfg4" and not a.splits and not a.entropy_top_m:
+    if a.workload == "cfg4" and not a.splits and not a.entropy_top_m and not a.rerank:
         try:
             import re
             with open(os.path.join(ROOT, "profiles", "k_logits_hist_cfg4_pmc.md")) as f:
@@ -123,7 +128,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
-                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "classifier_seed": W.classifier_seed(a.workload),
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
@@ -150,7 +155,10 @@ def main():
             if t.frontier()["n_frontier"].sum() == 0:
                 break
             t.expand_layer(sl[l], threads=1)
-        t.finalize()
+        if a.rerank:
+            t.finalize_rerank(a.rerank)
+        else:
+            t.finalize()
         cdt = time.perf_counter() - c0
         scored = int(t.audit()["scored"].sum())
         rec["cpu_baseline"] = {"value": scored / cdt, "unit": "nodes scored/s", "cores": 1, "kind": "oracle",

@@ -60,6 +60,7 @@ enum {
 #define C2T_MAX_HIDDEN 256
 #define C2T_MAX_BUDGET 1024
 #define C2T_MAX_CANDIDATES 2048 /* max_frontier * top_k */
+#define C2T_MAX_HISTORY 32768   /* max_depth * max_frontier * top_k with rerank = 1 */
 
 typedef struct {
   int32_t batch;        /* B: independent sequences                                   */
@@ -75,6 +76,9 @@ typedef struct {
                             M > 0: over the M most probable tokens, with the probabilities
                             of the full softmax (Eq. 2, line 2).  Then a row is never split
                             over workgroups: C2T_ERR_UNSUPPORTED if the vocabulary needs it */
+  int32_t rerank;        /* 1: keep every scored candidate of every layer in the workspace so that
+                            c2t_finalize_tree_reranked can be called (max_depth * max_frontier *
+                            top_k <= C2T_MAX_HISTORY); 0: only the tree                          */
 } c2t_config;
 
 /* Caller-owned [device] output buffers of c2t_finalize_tree, N = budget.
@@ -140,6 +144,17 @@ int c2t_get_candidates(c2t_ctx* ctx, const int32_t** n_cand, const int32_t** tok
 /* Emit the verification inputs of the tree built so far into caller-owned [device] buffers
  * (every field of `out` non-NULL). */
 int c2t_finalize_tree(c2t_ctx* ctx, const c2t_tree_out* out, void* stream);
+
+/* EAGLE-2-style reranking (Sec. 2.2: all candidate nodes are reranked and the top N selected),
+ * for a context created with rerank = 1: over every candidate that was given a confidence in any
+ * layer of this draft phase, kept by the prunings or not, the n_out (1..C2T_MAX_BUDGET) best by the
+ * smallest classifier logit on the candidate's path from the root (itself included).  That score
+ * never increases along a path, so with the order (score desc, depth asc, scoring order asc: slot,
+ * then rank in the row) every selected candidate's parent is selected before it: the result is a
+ * tree for any classifier, and the plain top-n_out by confidence for one that is monotone along
+ * paths (EAGLE-2's joint probability).  `out` as for c2t_finalize_tree with N = n_out; nodes in
+ * selection order.  Same place in the call order as c2t_finalize_tree. */
+int c2t_finalize_tree_reranked(c2t_ctx* ctx, const c2t_tree_out* out, int32_t n_out, void* stream);
 
 /* Per-launch accounting for benchmarks: [device] pointer to int32 [max_depth + 1];
  * entry l = number of logits rows layer l's expand consumed (sum over sequences of

@@ -30,7 +30,7 @@ class C2TConfig(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("vocab", ctypes.c_int32), ("max_frontier", ctypes.c_int32),
                 ("top_k", ctypes.c_int32), ("max_depth", ctypes.c_int32), ("budget", ctypes.c_int32),
                 ("hidden", ctypes.c_int32), ("logits_dtype", ctypes.c_int32), ("beta", ctypes.c_float),
-                ("entropy_top_m", ctypes.c_int32)]
+                ("entropy_top_m", ctypes.c_int32), ("rerank", ctypes.c_int32)]
 
 
 class _TreeOut(ctypes.Structure):
@@ -74,6 +74,7 @@ def load_library():
     L.c2t_get_frontier.argtypes = [vp, P(vp), P(vp), P(vp)]
     L.c2t_get_candidates.argtypes = [vp] + [P(vp)] * 7
     L.c2t_finalize_tree.argtypes = [vp, P(_TreeOut), vp]
+    L.c2t_finalize_tree_reranked.argtypes = [vp, P(_TreeOut), i32, vp]
     L.c2t_get_layer_rows.argtypes = [vp, P(vp)]
     L.c2t_set_row_splits.argtypes = [vp, i32, i32]
     L.c2t_profile_enable.argtypes = [vp, i32]
@@ -109,13 +110,13 @@ class C2TContext:
     """reset -> expand_layer x D -> finalize_tree on device memory (see include/c2t.h)."""
 
     def __init__(self, batch, vocab, max_frontier, top_k, max_depth, budget, hidden, dtype, beta,
-                 entropy_top_m=0, device="cuda:0"):
+                 entropy_top_m=0, rerank=0, device="cuda:0"):
         if not torch.cuda.is_available():
             raise RuntimeError("the C2T HIP path needs a GPU; there is no CPU fallback")
         self.L = load_library()
         self.device = torch.device(device)
         self.cfg = C2TConfig(batch, vocab, max_frontier, top_k, max_depth, budget, hidden,
-                             BF16 if dtype in (BF16, torch.bfloat16, "bf16") else F32, beta, entropy_top_m)
+                             BF16 if dtype in (BF16, torch.bfloat16, "bf16") else F32, beta, entropy_top_m, int(rerank))
         self.B, self.V, self.F, self.K, self.D, self.N, self.h = batch, vocab, max_frontier, top_k, max_depth, budget, hidden
         need = ctypes.c_size_t()
         _check(self.L.c2t_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(need)), "c2t_workspace_bytes")
@@ -175,8 +176,8 @@ class C2TContext:
             out[nm] = _view(p.value, shape, dt, self.device, self._ws)
         return out
 
-    def new_tree_out(self):
-        B, N, dev = self.B, self.N, self.device
+    def new_tree_out(self, N=None):
+        B, N, dev = self.B, (self.N if N is None else int(N)), self.device
         i32 = dict(dtype=torch.int32, device=dev)
         f32 = dict(dtype=torch.float32, device=dev)
         return dict(tokens=torch.empty((B, N), **i32), parent=torch.empty((B, N), **i32),
@@ -190,6 +191,14 @@ class C2TContext:
         o = _TreeOut(*[out[k].data_ptr() for k in
                        ("tokens", "parent", "position", "conf", "joint_prob", "entropy", "n_nodes", "mask", "status")])
         _check(self.L.c2t_finalize_tree(self.ctx, ctypes.byref(o), _stream_ptr(stream)), "c2t_finalize_tree")
+        return out
+
+    def finalize_tree_reranked(self, n_out, out=None, stream=None):
+        out = self.new_tree_out(n_out) if out is None else out
+        o = _TreeOut(*[out[k].data_ptr() for k in
+                       ("tokens", "parent", "position", "conf", "joint_prob", "entropy", "n_nodes", "mask", "status")])
+        _check(self.L.c2t_finalize_tree_reranked(self.ctx, ctypes.byref(o), int(n_out), _stream_ptr(stream)),
+               "c2t_finalize_tree_reranked")
         return out
 
     def layer_rows(self):

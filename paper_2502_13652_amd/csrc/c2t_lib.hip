@@ -20,7 +20,7 @@ using namespace c2t;
 namespace {
 
 constexpr size_t ALIGN = 256;
-static_assert(C2T_MAX_CANDIDATES == C2T_MAX_CANDIDATES_DEV && C2T_MAX_FRONTIER == SP_MAX_F && C2T_MAX_TOP_K == 64,
+static_assert(C2T_MAX_BUDGET == C2T_MAX_BUDGET_DEV && C2T_MAX_CANDIDATES == C2T_MAX_CANDIDATES_DEV && C2T_MAX_FRONTIER == SP_MAX_F && C2T_MAX_TOP_K == 64,
               "limits of the C ABI and of the kernels must agree");
 // Cell map of one workgroup.  bf16: four workgroups of 512 threads share the CU's 160 KB, each with the
 // 16 KB histogram, its static LDS (under 8 KB) and the map (2 bytes per 4 chunks): 16 KB at most.
@@ -39,7 +39,8 @@ inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
   size_t cls, n_nodes, nf0, nf1, tickets, row_tickets, row_info, status, n_cand, layer_rows;
-  size_t fr_tok, fr_pslot, fr_node, fr_P;
+  size_t fr_tok, fr_pslot, fr_node, fr_P, fr_hidx, fr_s;
+  size_t h_tok, h_par, h_P, h_H, h_z, h_s, h_ncand, h_pos;   // rerank contexts only
   size_t t_tok, t_parent, t_depth, t_P, t_H, t_z;
   size_t c_tok, c_p, c_P, c_H, c_z, c_kept;
   size_t part, part_topv, part_topi, tab_e;
@@ -64,10 +65,11 @@ int check_config(const c2t_config* c) {
     return C2T_ERR_INVALID_ARG;
   if (!(c->beta >= 0.0f && c->beta < 1.0f)) return C2T_ERR_INVALID_ARG;
   if (c->logits_dtype != C2T_F32 && c->logits_dtype != C2T_BF16) return C2T_ERR_INVALID_ARG;
-  if (c->top_k > c->vocab || c->entropy_top_m < 0) return C2T_ERR_INVALID_ARG;
+  if (c->top_k > c->vocab || c->entropy_top_m < 0 || (c->rerank != 0 && c->rerank != 1)) return C2T_ERR_INVALID_ARG;
   if (c->top_k > C2T_MAX_TOP_K || c->max_frontier > C2T_MAX_FRONTIER || c->hidden > C2T_MAX_HIDDEN ||
       c->budget > C2T_MAX_BUDGET || (int64_t)c->max_frontier * c->top_k > C2T_MAX_CANDIDATES)
     return C2T_ERR_UNSUPPORTED;
+  if (c->rerank && (int64_t)c->max_depth * c->max_frontier * c->top_k > C2T_MAX_HISTORY) return C2T_ERR_UNSUPPORTED;
   if (c->entropy_top_m != 0 && min_splits(*c) > 1) return C2T_ERR_UNSUPPORTED;   // the M largest logits of a row are found by one workgroup
   if ((int64_t)c->batch * c->max_frontier * min_splits(*c) > (1 << 24)) return C2T_ERR_UNSUPPORTED;
   return C2T_OK;
@@ -92,6 +94,13 @@ Layout make_layout(const c2t_config& c) {
   L.part_topv = take((size_t)L.partial_slots * K * 4);
   L.part_topi = take((size_t)L.partial_slots * K * 4);
   L.tab_e = take((size_t)HP_TAB_DOUBLES * 8);
+  L.fr_hidx = L.fr_s = L.h_tok = L.h_par = L.h_P = L.h_H = L.h_z = L.h_s = L.h_ncand = L.h_pos = 0;
+  if (c.rerank) {
+    const size_t H = B * (size_t)c.max_depth * F * K * 4;
+    L.fr_hidx = take(B * F * 4); L.fr_s = take(B * F * 4);
+    L.h_tok = take(H); L.h_par = take(H); L.h_P = take(H); L.h_H = take(H); L.h_z = take(H); L.h_s = take(H);
+    L.h_ncand = take(B * (size_t)c.max_depth * 4); L.h_pos = take(H);
+  }
   L.total = o;
   return L;
 }
@@ -146,7 +155,7 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   ScoreParams sp;
   sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
   sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
-  sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m;
+  sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m; sp.D = c.max_depth;
   if (c.logits_dtype == C2T_BF16) {
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
     sp.lds_bytes = (int)lds;
@@ -205,6 +214,13 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   s.layer_rows = (int32_t*)(w + L.layer_rows);
   s.fr_tok = (int32_t*)(w + L.fr_tok); s.fr_pslot = (int32_t*)(w + L.fr_pslot);
   s.fr_node = (int32_t*)(w + L.fr_node); s.fr_P = (float*)(w + L.fr_P);
+  s.fr_hidx = nullptr; s.fr_s = nullptr; s.h_tok = s.h_par = s.h_ncand = s.h_pos = nullptr; s.h_P = s.h_H = s.h_z = s.h_s = nullptr;
+  if (cfg->rerank) {
+    s.fr_hidx = (int32_t*)(w + L.fr_hidx); s.fr_s = (float*)(w + L.fr_s);
+    s.h_tok = (int32_t*)(w + L.h_tok); s.h_par = (int32_t*)(w + L.h_par); s.h_P = (float*)(w + L.h_P);
+    s.h_H = (float*)(w + L.h_H); s.h_z = (float*)(w + L.h_z); s.h_s = (float*)(w + L.h_s);
+    s.h_ncand = (int32_t*)(w + L.h_ncand); s.h_pos = (int32_t*)(w + L.h_pos);
+  }
   s.t_tok = (int32_t*)(w + L.t_tok); s.t_parent = (int32_t*)(w + L.t_parent); s.t_depth = (int32_t*)(w + L.t_depth);
   s.t_P = (float*)(w + L.t_P); s.t_H = (float*)(w + L.t_H); s.t_z = (float*)(w + L.t_z);
   s.c_tok = (int32_t*)(w + L.c_tok); s.c_p = (float*)(w + L.c_p); s.c_P = (float*)(w + L.c_P);
@@ -307,6 +323,22 @@ int c2t_finalize_tree(c2t_ctx* x, const c2t_tree_out* o, void* stream) {
   if (x->layer < 0) return C2T_ERR_STATE;
   TreeOut t{o->tokens, o->parent, o->position, o->conf, o->joint_prob, o->entropy, o->n_nodes, o->mask, o->status};
   hipLaunchKernelGGL(k_finalize, dim3(x->cfg.batch), dim3(256), 0, (hipStream_t)stream, x->st, t, x->cfg.budget);
+  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  x->finalized = true;
+  return C2T_OK;
+}
+
+int c2t_finalize_tree_reranked(c2t_ctx* x, const c2t_tree_out* o, int32_t n_out, void* stream) {
+  if (!x || !o) return C2T_ERR_INVALID_ARG;
+  if (!o->tokens || !o->parent || !o->position || !o->conf || !o->joint_prob || !o->entropy || !o->n_nodes ||
+      !o->mask || !o->status)
+    return C2T_ERR_INVALID_ARG;
+  if (n_out <= 0) return C2T_ERR_INVALID_ARG;
+  if (n_out > C2T_MAX_BUDGET) return C2T_ERR_UNSUPPORTED;
+  if (!x->cfg.rerank || x->layer < 0) return C2T_ERR_STATE;
+  TreeOut t{o->tokens, o->parent, o->position, o->conf, o->joint_prob, o->entropy, o->n_nodes, o->mask, o->status};
+  hipLaunchKernelGGL(k_finalize_rerank, dim3(x->cfg.batch), dim3(RR_NT), 0, (hipStream_t)stream, x->st, t, n_out,
+                     x->cfg.max_depth, x->cfg.max_frontier * x->cfg.top_k);
   if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
   x->finalized = true;
   return C2T_OK;

@@ -20,6 +20,12 @@ struct TreeState {            // device pointers into the workspace
   int32_t* fr_pslot;          // [B][F]
   int32_t* fr_node;           // [B][F]
   float* fr_P;                // [B][F]
+  int32_t* fr_hidx;           // [B][F] history index of the frontier node, -1 = root (rerank contexts only)
+  float* fr_s;                // [B][F] smallest classifier logit on its path, +inf for the root
+  // history of every scored candidate, [B][D][F*K] (rerank contexts only, else null)
+  int32_t* h_tok; int32_t* h_par; float* h_P; float* h_H; float* h_z; float* h_s;
+  int32_t* h_ncand;           // [B][D] candidates scored in each layer
+  int32_t* h_pos;             // [B][D*F*K] scratch of the reranking
   int32_t* t_tok;             // [B][N]
   int32_t* t_parent;
   int32_t* t_depth;
@@ -36,6 +42,10 @@ struct TreeState {            // device pointers into the workspace
 
 __global__ void k_reset(TreeState s, int B, int F, int D) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s.h_tok) {
+    if (i < B) { s.fr_hidx[(int64_t)i * F] = -1; s.fr_s[(int64_t)i * F] = INFINITY; }
+    for (int j = i; j < B * D; j += gridDim.x * blockDim.x) s.h_ncand[j] = 0;
+  }
   if (i < B) {
     s.n_nodes[i] = 0; s.nf[0][i] = 1; s.nf[1][i] = 0; s.tickets[i] = 0; s.status[i] = 0; s.n_cand[i] = 0;
     s.fr_tok[(int64_t)i * F] = -1; s.fr_pslot[(int64_t)i * F] = 0;
@@ -61,11 +71,12 @@ __device__ __forceinline__ float mlp_logit(const float* __restrict__ w, int h, f
 }
 
 constexpr int SP_MAX_F = 64;
+constexpr int C2T_MAX_BUDGET_DEV = 1024;                  // n_out limit of the reranking
 constexpr int C2T_MAX_CANDIDATES_DEV = 2048;              // F*K limit of the per-sequence step
 
 struct ScoreParams {
   RowPartial* part; float* part_topv; int32_t* part_topi;    // [launched row][split] records and their top-K lists
-  int nsplit, rows_per_seq, F, K, N, h, layer;
+  int nsplit, rows_per_seq, F, K, N, h, layer, D;
   int M;                                                     // 0: entropy over the whole row; M > 0: over the M largest logits
   int lds_bytes;                                             // dynamic LDS of the launch
   float z_beta;
@@ -185,6 +196,13 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
   const int64_t o = (int64_t)b * sp.F * K + (int64_t)f * K + tid;
   st_dev(s.c_tok + o, tok); st_dev(s.c_p + o, p32); st_dev(s.c_P + o, P32); st_dev(s.c_H + o, H); st_dev(s.c_z + o, z);
   if (tid == 0) st_dev(s.row_info + (int64_t)b * sp.F + f, (uint32_t)(bad ? 1u : 0u) | (fl & 2u));
+  if (s.h_tok) {                                             // keep the candidate for the reranking
+    const int FK = sp.F * K;
+    const int64_t hi = ((int64_t)b * sp.D + sp.layer) * FK + (int64_t)f * K + tid;
+    s.h_tok[hi] = tok; s.h_par[hi] = s.fr_hidx[(int64_t)b * sp.F + f];
+    s.h_P[hi] = P32; s.h_H[hi] = H; s.h_z[hi] = z;
+    s.h_s[hi] = fminf(s.fr_s[(int64_t)b * sp.F + f], z);
+  }
 }
 
 // ---- sequence level: both prunings of Sec. 4.2 with the node budget, tree append, next frontier.
@@ -217,7 +235,8 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   __shared__ int32_t n_surv, n_red, flags_or, sel_bin;
   __shared__ int32_t scan_w[NW];
   __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
-  __shared__ float new_P[SP_MAX_F];
+  __shared__ float new_P[SP_MAX_F], new_s[SP_MAX_F];
+  __shared__ int32_t new_hidx[SP_MAX_F];
 
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
   // the candidates' z and tokens are requested up front for all F*K slots: one memory round trip
@@ -317,10 +336,11 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
       const float z = mine ? sz[u] : 0.f;
       const int tok = mine ? stok[u] : 0, i = mine ? sidx[u] : 0;
       // what an appended node needs, requested before the ranking so that the latency overlaps it
-      float P = 0.f, H = 0.f; int par = -1;
+      float P = 0.f, H = 0.f, par_s = INFINITY; int par = -1;
       if (mine && sub == 0) {
         const int64_t o = (int64_t)b * FK + i;
         P = ld_dev(s.c_P + o); H = ld_dev(s.c_H + o); par = s.fr_node[(int64_t)b * F + i / K];
+        if (s.h_tok) par_s = s.fr_s[(int64_t)b * F + i / K];
       }
       int rank = 0;
       if (mine) {
@@ -356,6 +376,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
         s.t_tok[t] = tok; s.t_parent[t] = par; s.t_depth[t] = layer;
         s.t_P[t] = P; s.t_H[t] = H; s.t_z[t] = z;
         new_tok[rank] = tok; new_pslot[rank] = f; new_node[rank] = node; new_P[rank] = P;
+        new_hidx[rank] = layer * FK + i; new_s[rank] = fminf(par_s, z);
       }
     }
   }
@@ -364,8 +385,10 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     const int64_t o = (int64_t)b * F + tid;
     s.fr_tok[o] = new_tok[tid]; s.fr_pslot[o] = new_pslot[tid];
     s.fr_node[o] = new_node[tid]; s.fr_P[o] = new_P[tid];
+    if (s.h_tok) { s.fr_hidx[o] = new_hidx[tid]; s.fr_s[o] = new_s[tid]; }
   }
   if (tid == 0) {
+    if (s.h_tok) s.h_ncand[(int64_t)b * sp.D + layer] = ncand;
     s.n_nodes[b] = nn + n_keep;
     s.nf[(layer + 1) & 1][b] = n_keep;
     s.n_cand[b] = ncand;
@@ -450,6 +473,150 @@ __global__ __launch_bounds__(256) void k_finalize(TreeState s, TreeOut o, int N)
       j = s.t_parent[(int64_t)b * N + j];
     }
   }
+}
+
+
+// EAGLE-2-style reranking (Sec. 2.2), one workgroup of RR_NT threads per sequence: the n_out best of
+// every candidate scored in this draft phase under the order (s desc, history index asc), s = the
+// smallest classifier logit on the candidate's path (history index = layer * F*K + slot * K + rank
+// in the row, so index order is depth, then scoring order).  The n_out-th best key is found exactly by
+// a radix select over the order-preserving 32-bit keys of s (12 + 12 + 8 bits, an LDS histogram per
+// pass over the sequence's history); candidates above it are taken, those equal to it in index
+// order; the selection (<= 1024) is then ranked by counting.  Parents precede children because s
+// never increases along a path.
+constexpr int RR_NT = 1024;
+__global__ __launch_bounds__(RR_NT) void k_finalize_rerank(TreeState s, TreeOut o, int n_out, int D, int FK) {
+  constexpr int NW = RR_NT / WAVE;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  const int total = D * FK;
+  const int32_t* tok = s.h_tok + (int64_t)b * total; const int32_t* par = s.h_par + (int64_t)b * total;
+  const float* hs = s.h_s + (int64_t)b * total;
+  const int32_t* ncand = s.h_ncand + (int64_t)b * D;
+  int32_t* pos = s.h_pos + (int64_t)b * total;
+  __shared__ uint32_t dig[4096];
+  __shared__ int32_t scan_w[NW];
+  __shared__ int32_t sh_digit, sh_above, sh_total, sh_n;
+  __shared__ float sel_s[C2T_MAX_BUDGET_DEV];
+  __shared__ int32_t sel_i[C2T_MAX_BUDGET_DEV], sel_par[C2T_MAX_BUDGET_DEV], sel_depth[C2T_MAX_BUDGET_DEV];
+  // a thread owns a contiguous range of history indices, so that index order = thread order
+  const int per = (total + RR_NT - 1) / RR_NT, i0 = min(tid * per, total), i1 = min(i0 + per, total);
+  auto valid = [&](int i) { return (i % FK) < ncand[i / FK] && tok[i] >= 0; };
+  int my_valid = 0;
+  for (int i = i0; i < i1; ++i) my_valid += valid(i);
+  {
+    const int incl = wave_scan_incl(my_valid);
+    if (lane == WAVE - 1) scan_w[wid] = incl;
+    __syncthreads();
+    if (tid == 0) { int t = 0; for (int w = 0; w < NW; ++w) t += scan_w[w]; sh_n = t; }
+    __syncthreads();
+  }
+  const int n_all = sh_n, n = min(n_out, n_all);
+  uint32_t prefix = 0, care = 0;
+  int remaining = n;
+  if (n > 0 && n < n_all) {
+    const int shifts[3] = {20, 8, 0}, widths[3] = {12, 12, 8};
+#pragma unroll 1
+    for (int ps = 0; ps < 3; ++ps) {
+      const int shift = shifts[ps]; const uint32_t dmask = (1u << widths[ps]) - 1u;
+      for (int i = tid; i < 4096; i += RR_NT) dig[i] = 0u;
+      __syncthreads();
+      for (int i = i0; i < i1; ++i) {
+        if (!valid(i)) continue;
+        const uint32_t key = sortable_key(hs[i]);
+        if ((key & care) == prefix) atomicAdd(&dig[(key >> shift) & dmask], 1u);
+      }
+      __syncthreads();
+      {                                                      // thread t owns digits 4095-4t .. 4092-4t
+        uint32_t c[4]; int tot = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { c[j] = dig[4095 - (4 * tid + j)]; tot += (int)c[j]; }
+        const int incl = wave_scan_incl(tot);
+        if (lane == WAVE - 1) scan_w[wid] = incl;
+        __syncthreads();
+        int run = incl - tot;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) if (w < wid) run += scan_w[w];
+        if (run < remaining && run + tot >= remaining) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (run < remaining && run + (int)c[j] >= remaining) { sh_digit = 4095 - (4 * tid + j); sh_above = run; }
+            run += (int)c[j];
+          }
+        }
+        __syncthreads();
+      }
+      remaining -= sh_above;
+      prefix |= (uint32_t)sh_digit << shift; care |= dmask << shift;
+      __syncthreads();
+    }
+  }
+  // take: keys above the n-th best key, and the first `remaining` equal to it in index order
+  const bool take_all = n >= n_all;
+  int my_gt = 0, my_eq = 0;
+  for (int i = i0; i < i1; ++i) {
+    if (!valid(i)) continue;
+    const uint32_t key = sortable_key(hs[i]);
+    my_gt += take_all || key > prefix; my_eq += !take_all && key == prefix;
+  }
+  int before_gt, before_eq;
+  {
+    const int ig = wave_scan_incl(my_gt), ie = wave_scan_incl(my_eq);
+    __shared__ int32_t scan_e[NW];
+    if (lane == WAVE - 1) { scan_w[wid] = ig; scan_e[wid] = ie; }
+    __syncthreads();
+    before_gt = ig - my_gt; before_eq = ie - my_eq;
+    int tot_gt = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { if (w < wid) { before_gt += scan_w[w]; before_eq += scan_e[w]; } tot_gt += scan_w[w]; }
+    // slots: the keys above first (any order), then the ties in index order
+    int sg = before_gt, se = before_eq;
+    for (int i = i0; i < i1; ++i) {
+      if (!valid(i)) continue;
+      const uint32_t key = sortable_key(hs[i]);
+      int slot = -1;
+      if (take_all || key > prefix) slot = sg++;
+      else if (key == prefix) { if (se < remaining) slot = tot_gt + se; ++se; }
+      if (slot >= 0 && slot < n) { sel_s[slot] = hs[i]; sel_i[slot] = i; }
+    }
+  }
+  __syncthreads();
+  // rank the selection by (s desc, index asc) and emit
+  for (int e = tid; e < n; e += RR_NT) {
+    const float v = sel_s[e]; const int id = sel_i[e];
+    int rank = 0;
+    for (int q = 0; q < n; ++q) { const float vq = sel_s[q]; rank += (vq > v) || (vq == v && sel_i[q] < id); }
+    pos[id] = rank;
+    sel_depth[rank] = id / FK;
+    const int64_t t = (int64_t)b * n_out + rank, h = (int64_t)b * total + id;
+    o.tokens[t] = tok[id]; o.position[t] = id / FK + 1;
+    o.conf[t] = 1.0f / (1.0f + expf(-s.h_z[h])); o.joint_prob[t] = s.h_P[h]; o.entropy[t] = s.h_H[h];
+  }
+  for (int e = n + tid; e < n_out; e += RR_NT) {
+    const int64_t t = (int64_t)b * n_out + e;
+    o.tokens[t] = -1; o.parent[t] = -1; o.position[t] = 0; o.conf[t] = 0.f; o.joint_prob[t] = 0.f; o.entropy[t] = 0.f;
+  }
+  uint8_t* mk = o.mask + (int64_t)b * n_out * n_out;
+  {
+    const int64_t nb = (int64_t)n_out * n_out;               // zeroed with 4-byte stores where alignment allows
+    if ((((uintptr_t)mk) & 3) == 0) {
+      for (int64_t i = tid; i < nb / 4; i += RR_NT) ((uint32_t*)mk)[i] = 0u;
+      for (int64_t i = (nb / 4) * 4 + tid; i < nb; i += RR_NT) mk[i] = 0;
+    } else {
+      for (int64_t i = tid; i < nb; i += RR_NT) mk[i] = 0;
+    }
+  }
+  __threadfence_block();
+  __syncthreads();                                           // pos[] of every selected candidate is written
+  for (int e = tid; e < n; e += RR_NT) {
+    const int id = sel_i[e], rank = pos[id], pid = par[id];
+    const int prank = pid < 0 ? -1 : pos[pid];
+    sel_par[rank] = prank;
+    o.parent[(int64_t)b * n_out + rank] = prank;
+  }
+  __syncthreads();
+  for (int r = tid; r < n; r += RR_NT)
+    for (int j = r; j >= 0; j = sel_par[j]) mk[(int64_t)r * n_out + j] = 1;
+  if (tid == 0) { o.n_nodes[b] = n; o.status[b] = s.status[b]; }
 }
 
 }  // namespace c2t

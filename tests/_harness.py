@@ -23,7 +23,7 @@ def dtype_code(cfg):
 def make_gpu(cfg, cls, B=None, device="cuda:0"):
     from paper_2502_13652_amd import C2TContext
     ctx = C2TContext(B or cfg["B"], cfg["V"], cfg["F"], cfg["K"], cfg["D"], cfg["N"], cfg["h"], dtype_code(cfg),
-                     cfg["beta"], entropy_top_m=cfg.get("entropy_top_m", 0), device=device)
+                     cfg["beta"], entropy_top_m=cfg.get("entropy_top_m", 0), rerank=cfg.get("rerank", 0), device=device)
     ctx.set_classifier(*cls)
     return ctx
 

@@ -76,6 +76,57 @@ def test_entropy_over_top_1000_whole_trees(name, sample):
     assert total > 0
 
 
+def _compare_reranked(g, o, seqs, n_out, tag):
+    go = to_np(g.finalize_tree_reranked(n_out))
+    torch.cuda.synchronize()
+    oo = o.finalize_rerank(n_out)
+    for j, b in enumerate(seqs):
+        n = int(oo["n_nodes"][j])
+        assert int(go["n_nodes"][b]) == n, "%s n_out=%d seq %d: %d vs %d nodes" % (tag, n_out, b, go["n_nodes"][b], n)
+        for k in ("tokens", "parent", "position"):
+            np.testing.assert_array_equal(go[k][b], oo[k][j], err_msg="%s n_out=%d seq %d %s" % (tag, n_out, b, k))
+        np.testing.assert_array_equal(go["mask"][b], oo["mask"][j], err_msg="%s mask" % tag)
+        assert (go["status"][b] & 1) == (oo["status"][j] & 1)
+        for k in ("conf", "joint_prob", "entropy"):
+            np.testing.assert_allclose(go[k][b, :n], oo[k][j, :n], rtol=1e-5, err_msg="%s %s" % (tag, k))
+    return go
+
+
+@pytest.mark.parametrize("name,sample,eagle2", [("cfg1", 1, False), ("cfg2", 1, True), ("cfg3", 1, False), ("cfg4", 6, False),
+                                                ("cfg4", 4, True)])
+def test_reranked_finalize_against_oracle(name, sample, eagle2):
+    # Sec. 2.2, EAGLE-2's reranking phase over every scored candidate.  eagle2: the classifier is the
+    # joint probability itself and beta = 0, i.e. EAGLE-2's own expansion and rerank.
+    cfg = dict(W.CONFIGS[name], rerank=1)
+    if eagle2:
+        cfg["beta"] = 0.0
+        cfg["N"] = cfg["D"] * cfg["F"]                # the budget binds at the rerank, not in the expansion
+        W1 = np.zeros((cfg["h"], 3), np.float32); W1[0, 0] = 1
+        w2 = np.zeros(cfg["h"], np.float32); w2[0] = 1
+        cls = (W1, np.zeros(cfg["h"], np.float32), w2, 0.0)
+    else:
+        cls = W.classifier(cfg, W.classifier_seed(name))
+    rng = np.random.default_rng(5)
+    seqs = sorted(rng.choice(cfg["B"], sample, replace=False).tolist())
+    print("config", name, "rerank, eagle2 =", eagle2, "oracle on sequences", seqs, flush=True)
+    from _harness import make_oracle
+    layers = _layers(cfg, name, keep=cfg["B"] == 1)
+    g = make_gpu(cfg, cls)
+    o = make_oracle(cfg, cls, B=len(seqs))
+    g.reset(); o.reset()
+    for l in range(cfg["D"]):
+        x = layers(l)
+        g.expand_layer(x)
+        if o.frontier()["n_frontier"].sum() > 0:
+            o.expand_layer(W.as_numpy_bits(x[seqs]), threads=4)
+        del x
+    torch.cuda.synchronize()
+    total = int(o.audit()["scored"].max())
+    for n_out in sorted({1, 7, min(60, 1024), min(1024, max(1, total // 2)), min(1024, total + 3)}):
+        go = _compare_reranked(g, o, seqs, n_out, name)
+    print(name, "rerank: scored per sequence up to", total, "; last n_nodes", go["n_nodes"][seqs].tolist())
+
+
 def test_batched_chain_mode_ragged_lengths():
     # Sec. 5.5: one child per node; the classifier is an early-exit rule and sequences stop at
     # different depths.  Full batch on the GPU, the oracle replays a sample of the sequences.

@@ -31,7 +31,7 @@ def test_exports_every_declared_symbol(lib):
 def cfg(**kw):
     from paper_2502_13652_amd import C2TConfig
     base = dict(batch=2, vocab=1000, max_frontier=4, top_k=4, max_depth=3, budget=10, hidden=8, logits_dtype=1,
-                beta=0.5, entropy_top_m=0)
+                beta=0.5, entropy_top_m=0, rerank=0)
     base.update(kw)
     return C2TConfig(**base)
 
@@ -48,6 +48,11 @@ def test_config_validation(lib):
         assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**big)), ctypes.byref(need)) == -2, big
     assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=1000)), ctypes.byref(need)) == 0
     assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=-1)), ctypes.byref(need)) == -1
+    # reranking keeps every scored candidate: more workspace, bounded history
+    plain = ctypes.c_size_t(); lib.c2t_workspace_bytes(ctypes.byref(cfg()), ctypes.byref(plain))
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(rerank=1)), ctypes.byref(need)) == 0 and need.value > plain.value
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(rerank=2)), ctypes.byref(need)) == -1
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(rerank=1, max_depth=64, max_frontier=32, top_k=32)), ctypes.byref(need)) == -2
 
 
 def test_workspace_and_state_errors(lib):

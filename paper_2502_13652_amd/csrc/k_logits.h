@@ -654,6 +654,30 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
   return pat;
 }
 
+// The lane that holds the M-th largest logit: the sums over the logits it contributes to the top M
+// (from its top value down: positive magnitudes descending, or negative ones ascending), relative to
+// its top value vt.  Out of line: one lane per row gets here, and inlined its registers would be
+// charged to every workgroup's epilogue.
+template <int WPL>
+__device__ __noinline__ void top_m_boundary_lane(const double* __restrict__ tab, int tid, const uint32_t (&cw)[WPL], bool positive,
+                                                 int above, int M, double vt, double* zm_out, double* sm_out) {
+  double ep[WPL], en[WPL];
+  load_exp_factors<WPL>(tab, tid, ep, en);
+  double zm = 0.0, sm = 0.0;
+  int run = above;
+#pragma unroll 1
+  for (int jj = 0; jj < WPL; ++jj) {
+    const int j = positive ? WPL - 1 - jj : jj;
+    const int n = positive ? (int)(cw[j] & 0xffffu) : (int)(cw[j] >> 16), take = max(0, min(n, M - run));
+    run += n;
+    if (take) {
+      const double t = (double)take * (positive ? ep[j] : en[j]);
+      zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, !positive) - vt) * t;
+    }
+  }
+  *zm_out = zm; *sm_out = sm;
+}
+
 // One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
 // TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
@@ -741,7 +765,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   // S is accumulated against the largest value seen so far at each level (lane, wave, workgroup),
   // so every term has the same sign and nothing cancels: rows whose entropy is tiny keep their
   // relative accuracy.
-  double Z = 0.0, S = 0.0;
+  double Z = 0.0, S = 0.0, Zp = 0.0, Sp = 0.0;
   int lane_pos = 0, lane_neg = 0;
   float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
   uint32_t cw[WPL];                                     // low half: count of +|v_j|, high half: count of -|v_j|
@@ -765,12 +789,20 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     for (int j = 0; j < WPL; ++j) {
       const double vp = (double)hp_value_of_mag(WPL * tid + j, false);
       const double tp = (double)(cw[j] & 0xffffu) * evp[j];        // n * e^v (0 for an empty bin)
-      Z += tp; S += (vp - vt) * tp;
       const double tn = (double)(cw[j] >> 16) * evn[j];
-      Z += tn; S += (-vp - vt) * tn;
+      if (TOPM) {                                                  // the positive values' share kept apart
+        Zp += tp; Sp += (vp - vt) * tp;
+        Z += tn; S += (-vp - vt) * tn;
+      } else {
+        Z += tp; S += (vp - vt) * tp;
+        Z += tn; S += (-vp - vt) * tn;
+      }
       __builtin_amdgcn_sched_barrier(0);                           // one bin pair at a time: keeps live registers low
     }
   }
+  // TOPM: the lane's sums over its positive and over its negative values, relative to its top value
+  const double Zpos = Zp, Spos = Sp, Zneg = Z, Sneg = S;
+  if (TOPM) { Z += Zp; S += Sp; }
   const float vw = wave_max(vtop);                      // -inf only if the whole wave owns empty bins
   if (lane_pos | lane_neg) S += ((double)vtop - (double)vw) * Z;
   Z = wave_sum(Z); S = wave_sum(S);
@@ -854,27 +886,16 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     double zm = 0.0, sm = 0.0;
     const int above_p = tot_p - (before_p + incl_p), above_n = tot_p + before_n + incl_n - lane_neg;
     const double vt = (double)vtop;
-    if ((lane_pos > 0 && above_p < M) || (lane_neg > 0 && above_n < M)) {
-      double ep[WPL], en[WPL];
-      load_exp_factors<WPL>(tab_e, tid, ep, en);
-      if (lane_pos > 0 && above_p < M) {
-        int run = above_p;
-#pragma unroll
-        for (int j = WPL - 1; j >= 0; --j) {
-          const int n = (int)(cw[j] & 0xffffu), take = max(0, min(n, M - run));
-          run += n;
-          if (take) { const double t = (double)take * ep[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, false) - vt) * t; }
-        }
-      }
-      if (lane_neg > 0 && above_n < M) {
-        int run = above_n;
-#pragma unroll
-        for (int j = 0; j < WPL; ++j) {
-          const int n = (int)(cw[j] >> 16), take = max(0, min(n, M - run));
-          run += n;
-          if (take) { const double t = (double)take * en[j]; zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, true) - vt) * t; }
-        }
-      }
+    // A lane whose positive (negative) values all rank within the first M contributes the sums it
+    // already has; only the lane that holds the M-th largest logit walks its bins.
+    const bool part_p = lane_pos > 0 && above_p < M && above_p + lane_pos > M;
+    const bool part_n = lane_neg > 0 && above_n < M && above_n + lane_neg > M;
+    if (lane_pos > 0 && above_p + lane_pos <= M) { zm += Zpos; sm += Spos; }
+    if (lane_neg > 0 && above_n + lane_neg <= M) { zm += Zneg; sm += Sneg; }
+    if (part_p || part_n) {
+      double pz = 0.0, ps = 0.0;
+      top_m_boundary_lane<WPL>(tab_e, tid, cw, part_p, part_p ? above_p : above_n, M, vt, &pz, &ps);
+      zm += pz; sm += ps;
     }
     if (lane_pos | lane_neg) sm += (vt - (double)vw) * zm;
     zm = wave_sum(zm); sm = wave_sum(sm);

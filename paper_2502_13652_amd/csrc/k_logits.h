@@ -140,8 +140,8 @@ __device__ __forceinline__ int list_cells(const typename LogitTraits<DT>::key_t*
 }
 
 // Re-read the listed cells (CPC chunks each, one chunk per thread) and append their elements that
-// reach tau (exceed it, if strict) to the element list.  *sh_cnt must be 0 on entry (set before
-// a barrier); ends with a barrier.
+// reach tau (exceed it, if strict) to the element list, which overlays the cell map: the caller has
+// put a barrier after the last read of the map and after setting *sh_cnt = 0.  Ends with a barrier.
 template <int DT, int NT, int CPC>
 __device__ __forceinline__ void collect_cells(const uint4* __restrict__ rowp, int c0, int c1, int V, float tau, bool strict,
                                               const int32_t* cell_list, int n_cells, const SelectLds& sel, int32_t* sh_cnt) {
@@ -155,7 +155,6 @@ __device__ __forceinline__ void collect_cells(const uint4* __restrict__ rowp, in
     const int ch = c0 + chunk_of_cell<NT, CPC>(cell_list[tid / CPC], tid % CPC);
     if (ch < c1) { my_chunk = ch; q = rowp[ch]; }
   }
-  __syncthreads();                                           // the cell map is dead: the list may overlay it
   if (my_chunk >= 0) {
     float x[T::EPC];
     T::unpack(q, x);
@@ -778,13 +777,15 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     }
 #pragma unroll
     for (int j = 0; j < WPL; ++j) { lane_pos += (int)(cw[j] & 0xffffu); lane_neg += (int)(cw[j] >> 16); }
+    // typical rows leave the lanes (and whole waves) of the small magnitudes empty: they skip the fp64 work
+    if (lane_pos | lane_neg) {
 #pragma unroll
     for (int j = WPL - 1; j >= 0; --j)                  // lowest of the negative values last
       if (cw[j] >> 16) vtop = hp_value_of_mag(WPL * tid + j, true);
 #pragma unroll
     for (int j = 0; j < WPL; ++j)                       // highest of the positive values last
       if (cw[j] & 0xffffu) vtop = hp_value_of_mag(WPL * tid + j, false);
-    const double vt = (lane_pos | lane_neg) ? (double)vtop : 0.0;
+    const double vt = (double)vtop;
 #pragma unroll
     for (int j = 0; j < WPL; ++j) {
       const double vp = (double)hp_value_of_mag(WPL * tid + j, false);
@@ -798,6 +799,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
         Z += tn; S += (-vp - vt) * tn;
       }
       __builtin_amdgcn_sched_barrier(0);                           // one bin pair at a time: keeps live registers low
+    }
     }
   }
   // TOPM: the lane's sums over its positive and over its negative values, relative to its top value

@@ -397,15 +397,18 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   }
 }
 
-// Every thread's device-coherent stores are complete, then thread 0 takes a ticket: true for the
-// workgroup that took the last of `expected` (it resets the counter for the next layer).
+// Thread 0 takes a ticket once its wave's device-coherent stores are complete: true for the
+// workgroup that took the last of `expected` (it resets the counter for the next layer).  Every
+// store the ticket publishes is issued by wave 0 (at most 64 candidates or list entries, lanes
+// 0..63), whose own wait covers them; the other waves only meet at the barrier.
 __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
   __shared__ int32_t sh_last;
-  wait_vector_memory();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
-    if (sh_last) st_dev(ticket, 0);
+  if (threadIdx.x < WAVE) {
+    wait_vector_memory();
+    if (threadIdx.x == 0) {
+      sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
+      if (sh_last) st_dev(ticket, 0);
+    }
   }
   __syncthreads();
   return sh_last != 0;

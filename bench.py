@@ -31,6 +31,9 @@ def main():
                     help="M > 0: entropy over the M most probable tokens (Eq. 2, second line) instead of the whole row")
     ap.add_argument("--rerank", type=int, default=0,
                     help="n > 0: finish with the EAGLE-2-style reranking of all scored candidates (Sec. 2.2), n nodes out")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one draft phase in a HIP graph and time K replays (the per-launch kernel times for "
+                         "the roofline then come from K further, un-captured phases after the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
@@ -73,13 +76,34 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(a.steps * D)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if a.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                   # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ctx.profile_enable(a.steps * D)
+        for _ in range(a.steps):
+            step()
+        torch.cuda.synchronize()
+    else:
+        ctx.profile_enable(a.steps * D)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     k1_ms = ctx.profile_read(a.steps * D)
     ctx.profile_enable(0)
     rows = ctx.layer_rows().cpu().numpy()[:D].astype(np.int64)      # rows consumed by each layer's expand
@@ -128,7 +152,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
-                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "classifier_seed": W.classifier_seed(a.workload),
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "hip_graph": bool(a.graph), "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,

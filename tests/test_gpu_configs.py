@@ -167,3 +167,71 @@ def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():
             np.testing.assert_array_equal(outs[0][k], o[k], err_msg="split changes " + k)
         for k in ("conf", "joint_prob", "entropy"):
             np.testing.assert_allclose(outs[0][k], o[k], rtol=1e-5)
+
+
+LIMIT_CASES = {
+    # name: (B, V, dtype, D, F, K, h, beta, N): the compiled limits of the kernels, odd vocabularies
+    "max_candidates_bf16": (3, 20011, "bf16", 3, 64, 32, 256, 0.2, 1024),
+    "max_topk_bf16": (2, 5003, "bf16", 3, 32, 64, 64, 0.3, 100),
+    "max_candidates_f32": (2, 4099, "f32", 3, 64, 32, 16, 0.2, 200),
+    "wide_frontier_keep_all": (2, 9000, "bf16", 3, 64, 16, 8, 0.0, 1024),
+    "tiny_vocab": (5, 70, "bf16", 4, 8, 8, 4, 0.1, 30),
+    "budget_one": (4, 1000, "f32", 3, 4, 4, 4, 0.0, 1),
+}
+
+
+@pytest.mark.parametrize("case", sorted(LIMIT_CASES))
+def test_limits_of_the_kernels(case):
+    B, V, dtype, D, F, K, h, beta, N = LIMIT_CASES[case]
+    cfg = dict(idx=90 + sorted(LIMIT_CASES).index(case), B=B, V=V, dtype=dtype, D=D, F=F, K=K, h=h, beta=beta, N=N,
+               zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.1, desc=case)
+    total = 0
+    for seed in range(3):
+        cls = W.classifier(cfg, seed)
+        print("limits", case, "classifier seed", seed, flush=True)
+        base = _layers(cfg, case)
+
+        def padded(l, base=base):
+            # row stride rounded up to 16 bytes plus one spare chunk, padding poisoned with +inf
+            x = base(l)
+            epc = 8 if dtype == "bf16" else 4
+            stride = (V + epc - 1) // epc * epc + epc
+            xp = torch.full((B, F, stride), float("inf"), dtype=x.dtype, device=x.device)
+            xp[:, :, :V] = x
+            return xp[:, :, :V]
+        go, oo, audit = run_both(cfg, cls, padded, tag="%s seed %d" % (case, seed))
+        total += int(go["n_nodes"].sum())
+        print(case, "n_nodes", go["n_nodes"].tolist(), "scored", audit["scored"].tolist())
+    assert total > 0
+
+
+def test_reranked_finalize_at_the_history_limit():
+    # max_depth * max_frontier * top_k = 32768 = C2T_MAX_HISTORY, 1024 nodes out; keep-all classifier
+    # with many equal confidences (saturating hidden unit), so that ties at the n-th key occur
+    from _harness import make_oracle
+    B, V, D, F, K, h = 2, 5003, 16, 64, 32, 4
+    cfg = dict(idx=97, B=B, V=V, dtype="bf16", D=D, F=F, K=K, h=h, beta=0.0, N=1024, rerank=1,
+               zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="rerank limit")
+    W1 = np.zeros((h, 3), np.float32); W1[0, 0] = -1e6        # relu(b1 - 1e6 P) is 0 for all but vanishing P
+    b1 = np.zeros(h, np.float32); b1[0] = 1e-3
+    w2 = np.zeros(h, np.float32); w2[0] = 1.0
+    cls = (W1, b1, w2, 0.25)
+    base = _layers(cfg, "rerank_limit")
+
+    def padded(l):
+        x = base(l)
+        xp = torch.full((B, F, V + 13), float("inf"), dtype=x.dtype, device=x.device)
+        xp[:, :, :V] = x
+        return xp[:, :, :V]
+    g = make_gpu(cfg, cls)
+    o = make_oracle(cfg, cls)
+    g.reset(); o.reset()
+    for l in range(D):
+        x = padded(l)
+        g.expand_layer(x)
+        if o.frontier()["n_frontier"].sum() > 0:
+            o.expand_layer(W.as_numpy_bits(x), threads=4)
+    torch.cuda.synchronize()
+    print("scored per sequence", o.audit()["scored"].tolist(), flush=True)
+    for n_out in (1024, 333, 1):
+        _compare_reranked(g, o, list(range(B)), n_out, "rerank limit")

@@ -10,8 +10,9 @@
 #include <new>
 #include <vector>
 
-#include "../../include/c2t.h"
 #include <hip/hip_ext.h>
+
+#include "../../include/c2t.h"
 #include "k_logits.h"
 #include "k_tree.h"
 

@@ -14,18 +14,20 @@
 //    practical rows lie in 32 binades, |x| in [2^-25, 2^7).  The streaming loop only COUNTS
 //    values: one LDS atomic per element into an 8192-bin histogram (sign, 5 exponent bits,
 //    7 mantissa bits; two 16-bit counters per LDS word, overflow detected through the total).
-//    Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v
-//    are formed in fp64 from a table of e^v: exact counts, <= 8192 fp64 terms, independent
-//    of the order in which the elements were read.
-//  * any other row (fp32 logits; bf16 rows holding a logit outside the window, a zero, an
-//    infinity or a NaN): two passes over the segment with fp64 exponentials per element.
+//    Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v are formed in fp64 from small
+//    tables of exponentials: exact counts, <= 8192 fp64 terms, independent of the order in which
+//    the elements were read.  Logits below the window (zeros included) are counted apart:
+//    e^x = 1 + x to fp64 accuracy for |x| < 2^-25.
+//  * any other row (fp32 logits; bf16 rows holding a logit of magnitude >= 2^7, an infinity or
+//    a NaN, a value held by more than 65535 logits, or below-window logits that could rank among
+//    the K largest): two passes over the segment with fp64 exponentials per element.
 //
 // Top-K without data-dependent work in the streaming loop: the loop records the maximum of each
 // cell as a "cell key" in an LDS map.  A cell is one chunk (fp32) or the four chunks a lane reads
-// in four consecutive sweeps of the workgroup (bf16: chunks i, i+NT, i+2NT, i+3NT of the segment).  Afterwards a bound tau <= K-th largest logit is known
-// (exactly, from the histogram; or as the K-th largest per-lane maximum), only cells whose
-// key reaches tau can hold a top-K element, and those few cells are re-read and their elements
-// ranked exactly by (logit desc, id asc).
+// in four consecutive sweeps of the workgroup (bf16: chunks i, i+NT, i+2NT, i+3NT of the segment).
+// Afterwards a bound tau <= K-th largest logit is known (exactly, from the histogram; or as the
+// K-th largest per-lane maximum), only cells whose key reaches tau can hold a top-K element, and
+// those few cells are re-read and their elements ranked exactly by (logit desc, id asc).
 #pragma once
 #include "k_common.h"
 #include "k_tree.h"

@@ -1,6 +1,8 @@
-// Per-sequence kernels: merge the row partials, features + classifier (Eq. 1-3), the two
-// prunings of Sec. 4.2 with the node budget, tree append; reset; emission of the tree mask,
-// position ids and parent links.
+// Everything after a row's sums and top-K: the tail that the logits kernels run in place
+// (merge of split rows, features + classifier (Eq. 1-3) per row, the two prunings of Sec. 4.2 with
+// the node budget and the tree append per sequence, handed from workgroup to workgroup by tickets),
+// and the small kernels: reset, emission of the tree mask, position ids and parent links, and the
+// EAGLE-2-style reranked emission (Sec. 2.2).
 #pragma once
 #include "k_common.h"
 

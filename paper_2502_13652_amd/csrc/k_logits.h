@@ -509,6 +509,7 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * (DT == 1 ? 2 : 4));
   const Segment sg = make_segment<T::EPC>(V, split, cps);
   __shared__ RowResult rr;
+  if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else generic_segment<DT, NT, 1>(rowp, V, K, sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
   finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
@@ -973,6 +974,7 @@ __global__ __launch_bounds__(NT, 8) void k_logits_hist(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
   const Segment sg = make_segment<8>(V, split, cps);
   __shared__ RowResult rr;
+  if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else hist_segment<NT, TOPM>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);

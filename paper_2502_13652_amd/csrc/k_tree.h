@@ -89,6 +89,7 @@ struct ScoreParams {
 struct RowResult {
   RowPartial part;
   double ZM, SM;      // the sums of Z and S restricted to the M largest logits (Eq. 2, second line); M > 0 only
+  float parent_P;     // joint probability of the row's frontier node, fetched when the workgroup starts
   float topv[64];
   int32_t topi[64];
 };
@@ -177,7 +178,7 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
                                           const float* __restrict__ w) {
   const int tid = threadIdx.x, K = sp.K;
   if (tid >= K) return;
-  const float parP = s.fr_P[(int64_t)b * sp.F + f];
+  const float parP = rr.parent_P;
   const double R = rr.part.ref, Z = rr.part.Z;
   const uint32_t fl = rr.part.flags;
   const bool bad = (fl & 1u) != 0 || !(Z > 0.0) || !(R > -INFINITY) || !(R < INFINITY);
@@ -256,6 +257,9 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   const uint32_t info = tid < F ? ld_dev(s.row_info + (int64_t)b * F + tid) : 0u;
   const int nf = s.nf[layer & 1][b];
   const int nn = s.n_nodes[b];
+  // the kept flags start at zero (all F*K slots: slots of unused rows are unspecified anyway); stored
+  // now, so that they are long complete when the ranking stores the ones
+  for (int i = tid; i < FK; i += NT) s.c_kept[(int64_t)b * FK + i] = 0;
   if (tid == 0) { n_surv = 0; n_red = 0; flags_or = 0; sel_bin = 0; }
   for (int i = tid; i < PRUNE_HIST_WORDS; i += NT) hist[i] = 0u;
   __syncthreads();
@@ -267,7 +271,6 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   for (int k = 0; k < PER; ++k) {
     const int i = tid + k * NT;
     if (k < per && i < ncand) {
-      s.c_kept[(int64_t)b * FK + i] = 0;
       if (my_tok[k] >= 0 && my_z[k] > z_beta) {
         const int u = atomicAdd(&n_surv, 1);
         sz[u] = my_z[k]; stok[u] = my_tok[k]; sidx[u] = i;

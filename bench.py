@@ -31,6 +31,9 @@ def main():
                     help="M > 0: entropy over the M most probable tokens (Eq. 2, second line) instead of the whole row")
     ap.add_argument("--rerank", type=int, default=0,
                     help="n > 0: finish with the EAGLE-2-style reranking of all scored candidates (Sec. 2.2), n nodes out")
+    ap.add_argument("--mask-frac", type=float, default=0.0,
+                    help="fraction of the vocabulary (a seeded, scattered set of tokens, the same in every row) whose "
+                         "logits are -inf, as under constrained decoding")
     ap.add_argument("--graph", action="store_true",
                     help="capture one draft phase in a HIP graph and time K replays (the per-launch kernel times for "
                          "the roofline then come from K further, un-captured phases after the timed region)")
@@ -57,6 +60,11 @@ def main():
     # chosen on (torch's CPU and GPU generators differ; a GPU-generated cfg3 tree dies at the root).
     gen = "cpu" if B * F * V * D * esz <= (256 << 20) else dev
     layers = [W.logits_layer(cfg, l, device=gen).to(dev) for l in range(D)]
+    if a.mask_frac > 0:
+        g = torch.Generator(device="cpu").manual_seed(20250213)
+        masked = (torch.rand(V, generator=g) < a.mask_frac).to(dev)
+        for x in layers:
+            x[..., :V].masked_fill_(masked, float("-inf"))
     ctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"],
                      entropy_top_m=a.entropy_top_m, rerank=1 if a.rerank else 0, device=dev)
     ctx.set_classifier(*cls)
@@ -134,7 +142,7 @@ def main():
     # HBM traffic per launch from the committed counter pass (rocprofv3 --pmc FETCH_SIZE, scaled by the
     # factor the same counter shows for the plain read kernel); only for the workload it was taken on
     traffic = None
-    if a.workload == "cfg4" and not a.splits and not a.entropy_top_m and not a.rerank:
+    if a.workload == "cfg4" and not a.splits and not a.entropy_top_m and not a.rerank and not a.mask_frac:
         try:
             import re
             with open(os.path.join(ROOT, "profiles", "k_logits_hist_cfg4_pmc.md")) as f:
@@ -152,7 +160,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
-                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "hip_graph": bool(a.graph), "classifier_seed": W.classifier_seed(a.workload),
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "mask_frac": a.mask_frac, "hip_graph": bool(a.graph), "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,

@@ -17,10 +17,12 @@
 //    Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v are formed in fp64 from small
 //    tables of exponentials: exact counts, <= 8192 fp64 terms, independent of the order in which
 //    the elements were read.  Logits below the window (zeros included) are counted apart:
-//    e^x = 1 + x to fp64 accuracy for |x| < 2^-25.
-//  * any other row (fp32 logits; bf16 rows holding a logit of magnitude >= 2^7, an infinity or
-//    a NaN, a value held by more than 65535 logits, or below-window logits that could rank among
-//    the K largest): two passes over the segment with fp64 exponentials per element.
+//    e^x = 1 + x to fp64 accuracy for |x| < 2^-25.  So are logits equal to -inf (the masked
+//    tokens of constrained decoding): they add nothing to either sum and rank after every
+//    finite logit.
+//  * any other row (fp32 logits; bf16 rows holding a finite logit of magnitude >= 2^7, +inf or
+//    a NaN, a value held by more than 65535 logits, or below-window or -inf logits that could
+//    rank among the K largest): two passes over the segment with fp64 exponentials per element.
 //
 // Top-K without data-dependent work in the streaming loop: the loop records the maximum of each
 // cell as a "cell key" in an LDS map.  A cell is one chunk (fp32) or the four chunks a lane reads
@@ -607,26 +609,72 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 struct HistLane {
   uint32_t mag_max = 0u;            // packed running max of |code| (two halves): NaN, inf and |x| >= 2^7 show here
   uint32_t M2 = HP_F16_NEG_INF2;    // packed running maximum of the bf16 patterns (compared as fp16 patterns)
-  int n_tiny = 0;                   // logits with |x| < 2^-25 (zeros included): e^x = 1 + x to fp64 accuracy
-  double s_tiny = 0.0;              // their sum
+  int n_tiny = 0;                   // low half: logits with |x| < 2^-25 (zeros included), e^x = 1 + x to fp64 accuracy;
+                                    // high half: logits equal to -inf (masked tokens: probability 0, ranked last)
+  double s_tiny = 0.0;              // sum of the former
 };
 
-// One element at a time: used for chunks that hold a logit below the window and for a row's
-// partial last chunk.  Returns the maximum of the valid elements as a packed pattern.
-__device__ __forceinline__ uint32_t hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
-  float x[8];
-  LogitTraits<1>::unpack(q, x);
-  float cm = -INFINITY;
-#pragma unroll 1
-  for (int j = 0; j < n_valid; ++j) {
-    const uint32_t code = __float_as_uint(x[j]) >> 16, mag = code & 0x7fffu;
-    a.mag_max = pk_max_u16(a.mag_max, mag);
-    cm = fmaxf(cm, x[j]);
-    if (mag < HP_MAG_LO) { a.n_tiny += 1; a.s_tiny += (double)x[j]; }
-    else atomicAdd(&hist[code & (HP_WORDS - 1)], (code & 0x8000u) ? 0x10000u : 1u);
+// Chunks that hold a logit outside the window, and a row's partial last chunk (n_valid < 8).  Out
+// of line, with the lane's running values passed and returned by value: typical rows never get
+// here, and inlined at each of the streaming loop's sites this code costs the whole kernel registers.
+// If everything outside the window is -inf (masked tokens), those logits are counted apart and the
+// rest of the chunk is counted as in hist_chunk; otherwise one element at a time.
+// pat: the maximum of the valid elements as a packed pattern; where all of them are -inf, a value
+// below every finite logit of the window path (a cell key only has to be an upper bound).
+struct HistOutside { uint32_t pat, mag_max; int n_tiny; double s_tiny; };
+__device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uint32_t mag_max, int n_tiny, double s_tiny,
+                                                       uint32_t* __restrict__ hist) {
+  constexpr uint32_t TWO2 = 0x00020002u, BIAS2 = ((0x10000u - 2u * HP_MAG_LO) & 0xffffu) * 0x00010001u;
+  constexpr uint32_t LOWEST = 0x8000u | (HP_MAG_LO + HP_MAG_SPAN - 1);   // the lowest value of the window stands in for -inf
+  HistOutside r;
+  r.mag_max = mag_max; r.n_tiny = n_tiny; r.s_tiny = s_tiny;
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  if (n_valid == 8) {
+    uint32_t w2[4], inf_lo[4], inf_hi[4], n_inf = 0u, dm = 0u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      inf_lo[j] = (w[j] & 0xffffu) == 0xff80u ? ~0u : 0u;
+      inf_hi[j] = (w[j] >> 16) == 0xff80u ? ~0u : 0u;
+      w2[j] = w[j];
+      if (inf_lo[j]) w2[j] = (w2[j] & 0xffff0000u) | LOWEST;
+      if (inf_hi[j]) w2[j] = (w2[j] & 0x0000ffffu) | (LOWEST << 16);
+      n_inf -= inf_lo[j] + inf_hi[j];                           // the masks are 0 or -1
+      dm = pk_max_u16(dm, pk_mad_u16(w2[j], TWO2, BIAS2));
+    }
+    if (!(dm & 0xE000E000u)) {
+      r.n_tiny += (int)(n_inf << 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {                             // masked lanes stay out of the atomics (no same-address pile-up)
+        if (!inf_hi[j]) atomicAdd(&hist[bits_16_27(w2[j])], hist_increment((int32_t)w2[j] >> 31, 0x10000u));
+        if (!inf_lo[j]) atomicAdd(&hist[w2[j] & (HP_WORDS - 1)], hist_increment(__builtin_amdgcn_sbfe((int32_t)w2[j], 15, 1), 0x10000u));
+      }
+      r.pat = pk_max_f16(pk_max_f16(w2[0], w2[1]), pk_max_f16(w2[2], w2[3]));
+      return r;
+    }
   }
-  const uint32_t c16 = __float_as_uint(cm) >> 16;
-  return c16 | (c16 << 16);
+  float cm = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float x = (j & 1) ? bf16_hi(w[j >> 1]) : bf16_lo(w[j >> 1]);
+    const uint32_t code = __float_as_uint(x) >> 16, mag = code & 0x7fffu;
+    if (j < n_valid) {
+      if (code == 0xff80u) r.n_tiny += 0x10000;
+      else {
+        r.mag_max = pk_max_u16(r.mag_max, mag);
+        cm = fmaxf(cm, x);
+        if (mag < HP_MAG_LO) { r.n_tiny += 1; r.s_tiny += (double)x; }
+        else atomicAdd(&hist[code & (HP_WORDS - 1)], (code & 0x8000u) ? 0x10000u : 1u);
+      }
+    }
+  }
+  const uint32_t c16 = cm == -INFINITY ? (HP_F16_NEG_INF2 & 0xffffu) : __float_as_uint(cm) >> 16;
+  r.pat = c16 | (c16 << 16);
+  return r;
+}
+__device__ __forceinline__ uint32_t hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
+  const HistOutside r = hist_chunk_outside(q, n_valid, a.mag_max, a.n_tiny, a.s_tiny, hist);
+  a.mag_max = r.mag_max; a.n_tiny = r.n_tiny; a.s_tiny = r.s_tiny;
+  return r.pat;
 }
 
 // Counts the values of a whole chunk; returns the chunk maximum as a packed pattern (both halves
@@ -695,7 +743,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   __shared__ double red_d[2][NW], sum_d[2], sum_m[2];
   __shared__ float red_v[NW];
   __shared__ uint32_t red_u[NW], red_m[NW];
-  __shared__ int32_t sh_ntiny;
+  __shared__ int32_t sh_ntiny, sh_nninf;
   __shared__ double sh_stiny;
   __shared__ int32_t cell_list[SEL_CELL_CAP];
   __shared__ int32_t scan_tmp[2][NW];
@@ -705,7 +753,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 
 #pragma unroll
   for (int j = 0; j < WPL; ++j) hist[tid + j * NT] = 0u;
-  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_ntiny = 0; sh_stiny = 0.0; }
+  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_ntiny = 0; sh_nninf = 0; sh_stiny = 0.0; }
   __syncthreads();
 
   // ---------------- streaming loop: count values, record cell maxima ----------------
@@ -744,11 +792,13 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       if (g + 3 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qd, g + 3 * NT));
       else if (g + 3 * NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
       *mp = (uint16_t)pk_max_f16(key, key >> 16);
+      a.M2 = pk_max_f16(a.M2, key);                       // the partial chunk's maximum is in no other running value
     }
 #undef C2T_COUNT
 #undef C2T_LOAD
   }
-  if (a.n_tiny) { atomicAdd(&sh_ntiny, a.n_tiny); atomicAdd(&sh_stiny, a.s_tiny); }
+  if (a.n_tiny & 0xffff) { atomicAdd(&sh_ntiny, a.n_tiny & 0xffff); atomicAdd(&sh_stiny, a.s_tiny); }
+  if (a.n_tiny >> 16) atomicAdd(&sh_nninf, a.n_tiny >> 16);
 
   // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  The table
   // loads for their e^v are issued now so that their latency hides behind the barrier.
@@ -821,7 +871,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   for (int w = 0; w < NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m2 = pk_max_f16(m2, red_m[w]); }
   const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16);
   const float m = fmaxf(bf16_lo(m2), bf16_hi(m2));      // exact whenever the row stays on this path
-  const int n_tiny = sh_ntiny;
+  const int n_tiny = sh_ntiny, n_ninf = sh_nninf;
   int before_p = 0, before_n = 0, tot_p = 0, tot_n = 0; // counts in lower lanes / in the whole segment
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
@@ -872,13 +922,15 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     }
   }
   __syncthreads();
-  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, infinities, NaN), if a
-  // 16-bit counter overflowed (the total is then off by a multiple of 65535 or 65536), or if logits
+  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, +inf, NaN), if a
+  // 16-bit counter overflowed (the total is then off by a multiple of 65535 or 65536), if logits
   // below the window exist and the K-th largest logit is not a positive window value (then they
-  // could be among the top K, which the histogram cannot rank).
+  // could be among the top K, which the histogram cannot rank), or if fewer than K logits are
+  // finite while some are -inf (the top K then ends with -inf entries).
   const int n_elems = (sg.tail_chunk >= 0 ? (sg.ncell - 1) * 8 + sg.tail_valid : sg.ncell * 8);
   // With the entropy over the M largest logits: also if logits below the window could be among them.
-  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS) ||
+  if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny + n_ninf != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS) ||
+      (n_ninf > 0 && sh_tau_rank < 0) ||
       (TOPM && n_tiny > 0 && tot_p < M)) {
     __syncthreads();
     generic_segment<1, NT, HP_CPC>(rowp, V, K, M, sg, map_lds, sel, rr, 2u);

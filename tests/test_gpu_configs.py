@@ -58,6 +58,30 @@ def test_batched_configs_full_size_sampled_oracle(name, sample):
     print(name, "nodes/seq mean %.1f" % n.mean(), "min margins", audit["min_thr_margin"].min(), audit["min_rank_gap"].min())
 
 
+@pytest.mark.parametrize("name,sample,frac", [("cfg2", 1, 0.3), ("cfg4", 6, 0.01), ("cfg4", 6, 0.9)])
+def test_masked_vocabulary_whole_trees(name, sample, frac):
+    """Constrained decoding: the same scattered set of tokens has logit -inf in every row (probability
+    0, ranked after every finite logit).  The bf16 rows stay on the histogram path."""
+    cfg = W.CONFIGS[name]
+    cls = W.classifier(cfg, W.classifier_seed(name))
+    rng = np.random.default_rng(11)
+    seqs = sorted(rng.choice(cfg["B"], sample, replace=False).tolist())
+    masked = torch.from_numpy(rng.random(cfg["V"]) < frac).cuda()
+    plain = _layers(cfg, name, keep=False)
+
+    def layers(l):
+        x = plain(l).clone()
+        x.masked_fill_(masked, float("-inf"))
+        return x
+    print("config", name, "masked fraction", frac, "oracle on sequences", seqs, flush=True)
+    go, oo, audit = run_both(cfg, cls, layers, seqs=seqs, tag="%s masked %g" % (name, frac))
+    assert go["n_nodes"].sum() > 0
+    k = int(go["n_nodes"][seqs[0]])
+    assert not masked[torch.from_numpy(go["tokens"][seqs[0], 1:k].astype(np.int64)).cuda()].any()   # no masked token drafted
+    if cfg["dtype"] == "bf16":
+        assert not (go["status"] & 2).any()               # no row left the histogram path
+
+
 @pytest.mark.parametrize("name,sample", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 6)])
 def test_entropy_over_top_1000_whole_trees(name, sample):
     # the paper's own configuration of the H feature: Eq. 2, second line with M = 1000

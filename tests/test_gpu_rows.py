@@ -30,6 +30,11 @@ def adversarial_rows(V, rng, bf16):
     add("ties_coarse", np.round(2 * rng.standard_normal(V)))            # a handful of distinct values
     mi = 2 * rng.standard_normal(V); mi[rng.random(V) < 0.3] = -np.inf
     add("minus_inf_30pct", mi)
+    mi9 = 2 * rng.standard_normal(V); mi9[rng.random(V) < 0.9] = -np.inf   # most chunks hold nothing but -inf
+    add("minus_inf_90pct", mi9)
+    mit = 2 * rng.standard_normal(V); mit[rng.random(V) < 0.2] = -np.inf; mit[rng.random(V) < 0.05] = 0.0
+    mit[V - 1] = -np.inf; mit[V - 2] = 7.0                                # masked, zero and largest logits side by side
+    add("minus_inf_with_zeros", mit)
     mi2 = np.full(V, -np.inf); mi2[[0, V // 2, V - 1]] = [1.0, 2.0, 2.0]
     add("only_three_finite", mi2)
     add("sorted_desc", np.sort(3 * rng.standard_normal(V))[::-1].copy())

@@ -120,10 +120,38 @@ def main():
     bytes_layer = rows * V * esz
     k1_total_s = k1_ms.sum() / 1e3
     achieved = bytes_layer.sum() * a.steps / k1_total_s / 1e9       # GB/s over every logits-pass launch
-    full = rows == B * F
     per_layer = [dict(layer=int(l), rows=int(rows[l]), mbytes=round(bytes_layer[l] / 1e6, 2),
                       us=round(float(k1_ms[:, l].mean() * 1e3), 2),
                       gbps=round(float(bytes_layer[l] / (k1_ms[:, l].mean() / 1e3) / 1e9), 1)) for l in range(D)]
+
+    # Full layers (every sequence with F valid rows), the unit the HBM roofline is stated on: the same
+    # logits and classifier with beta = 0, so that every candidate survives the first pruning and the
+    # frontiers stay full until the budget is used up.  Outside the timed region.
+    full_layer = None
+    n_full = min(D - 1, N // F) if B > 1 else 0
+    if n_full >= 1 and not a.mask_frac:
+        fctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, 0.0,
+                          entropy_top_m=a.entropy_top_m, device=dev)
+        fctx.set_classifier(*cls)
+        if a.splits:
+            fctx.set_row_splits(*[int(x) for x in a.splits.split(",")])
+        reps = max(3, a.steps // 2)
+        for timed in (False, True):
+            if timed:
+                fctx.profile_enable(reps * (1 + n_full))
+            for _ in range(reps):
+                fctx.reset()
+                for l in range(1 + n_full):
+                    fctx.expand_layer(layers[l])
+            torch.cuda.synchronize()
+        f_ms = np.array(fctx.profile_read(reps * (1 + n_full)), np.float64).reshape(reps, 1 + n_full)[:, 1:]
+        f_rows = fctx.layer_rows().cpu().numpy()[1:1 + n_full].astype(np.int64)
+        assert (f_rows == B * F).all(), f_rows
+        fctx.profile_enable(0)
+        fb = float(B * F * V * esz)
+        full_layer = {"rows": int(B * F), "bytes": fb, "launches": int(f_ms.size), "us": float(f_ms.mean() * 1e3),
+                      "gbps": fb / (f_ms.mean() / 1e3) / 1e9, "frac": fb / (f_ms.mean() / 1e3) / 1e9 / HBM_PEAK_GBPS}
+        del fctx
 
     # practical ceiling: plain streaming read of a buffer larger than the last-level cache
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -167,7 +195,7 @@ def main():
                      "kernel": "k_logits_hist<512>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>", "launches": int(a.steps * D),
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),
-                     "full_layer_gbps": float(np.mean([p["gbps"] for p, f in zip(per_layer, full) if f])) if full.any() else None,
+                     "full_layer": full_layer,
                      "stream_read_gbps": stream_gbps, "per_layer": per_layer},
     }
 

@@ -224,6 +224,26 @@ def main():
         rec["cpu_baseline"] = {"value": scored / cdt, "unit": "nodes scored/s", "cores": 1, "kind": "oracle",
                                "sample": "whole draft phases of the first %d of %d sequences of %s, %d candidates, %.1f s"
                                          % (nseq, B, a.workload, scored, cdt)}
+        # the same oracle with the (independent) sequences sharded over the host's cores
+        nthr = min(16, os.cpu_count() or 1, B)
+        if nthr > 1:
+            nseq_all = min(B, nseq * nthr)
+            sl = [W.as_numpy_bits(x[:nseq_all].cpu()) for x in layers]
+            t = RefTree(nseq_all, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, cfg["beta"])
+            if a.entropy_top_m:
+                t.set_entropy_top_m(a.entropy_top_m)
+            t.set_classifier(*cls)
+            t.reset()
+            c0 = time.perf_counter()
+            for l in range(D):
+                if t.frontier()["n_frontier"].sum() == 0:
+                    break
+                t.expand_layer(sl[l], threads=nthr)
+            t.finalize_rerank(a.rerank) if a.rerank else t.finalize()
+            cdt = time.perf_counter() - c0
+            scored = int(t.audit()["scored"].sum())
+            rec["cpu_baseline"]["sharded"] = {"value": scored / cdt, "cores": nthr,
+                                              "sample": "%d sequences, %d candidates, %.1f s" % (nseq_all, scored, cdt)}
     print(json.dumps(rec))
 
 

@@ -96,9 +96,9 @@ typedef struct {
                           the root is not a slot (every node attends to it)            */
   uint32_t* status;    /* [B] bit 0: a consumed row held NaN / +inf / no finite logit;
                           bit 1 (informational): a bf16 row took the slower two-pass
-                          path (a logit of magnitude >= 2^7 other than -inf; one value
-                          held by more than 65535 logits; logits below 2^-25 in magnitude
-                          or -inf among the K largest)                                 */
+                          path (a logit >= 2^7 or in (-2^10, -2^7]; one value held by
+                          more than 65535 logits; logits below 2^-25 in magnitude, -inf
+                          or <= -2^10 among the K largest)                             */
 } c2t_tree_out;
 
 /* Bytes of device workspace a context of this configuration needs.  [host] out. */

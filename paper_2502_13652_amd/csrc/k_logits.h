@@ -17,11 +17,11 @@
 //    Afterwards Z = sum_v n_v e^v and S = sum_v n_v (v-m) e^v are formed in fp64 from small
 //    tables of exponentials: exact counts, <= 8192 fp64 terms, independent of the order in which
 //    the elements were read.  Logits below the window (zeros included) are counted apart:
-//    e^x = 1 + x to fp64 accuracy for |x| < 2^-25.  So are logits equal to -inf (the masked
-//    tokens of constrained decoding): they add nothing to either sum and rank after every
-//    finite logit.
-//  * any other row (fp32 logits; bf16 rows holding a finite logit of magnitude >= 2^7, +inf or
-//    a NaN, a value held by more than 65535 logits, or below-window or -inf logits that could
+//    e^x = 1 + x to fp64 accuracy for |x| < 2^-25.  So are masked logits, -inf or a finite
+//    x <= -2^10 (the masked tokens of constrained decoding): they add exactly nothing to either
+//    sum and rank after every window value.
+//  * any other row (fp32 logits; bf16 rows holding a logit >= 2^7 or in (-2^10, -2^7], +inf or
+//    a NaN, a value held by more than 65535 logits, or below-window or masked logits that could
 //    rank among the K largest): two passes over the segment with fp64 exponentials per element.
 //
 // Top-K without data-dependent work in the streaming loop: the loop records the maximum of each
@@ -610,22 +610,27 @@ struct HistLane {
   uint32_t mag_max = 0u;            // packed running max of |code| (two halves): NaN, inf and |x| >= 2^7 show here
   uint32_t M2 = HP_F16_NEG_INF2;    // packed running maximum of the bf16 patterns (compared as fp16 patterns)
   int n_tiny = 0;                   // low half: logits with |x| < 2^-25 (zeros included), e^x = 1 + x to fp64 accuracy;
-                                    // high half: logits equal to -inf (masked tokens: probability 0, ranked last)
+                                    // high half: masked logits (see hp_masked: probability 0, ranked last)
   double s_tiny = 0.0;              // sum of the former
 };
 
 // Chunks that hold a logit outside the window, and a row's partial last chunk (n_valid < 8).  Out
 // of line, with the lane's running values passed and returned by value: typical rows never get
 // here, and inlined at each of the streaming loop's sites this code costs the whole kernel registers.
-// If everything outside the window is -inf (masked tokens), those logits are counted apart and the
-// rest of the chunk is counted as in hist_chunk; otherwise one element at a time.
-// pat: the maximum of the valid elements as a packed pattern; where all of them are -inf, a value
+// If everything outside the window is masked (see hp_masked), those logits are counted apart and
+// the rest of the chunk is counted as in hist_chunk; otherwise one element at a time.
+// pat: the maximum of the valid elements as a packed pattern; where all of them are masked, a value
 // below every finite logit of the window path (a cell key only has to be an upper bound).
 struct HistOutside { uint32_t pat, mag_max; int n_tiny; double s_tiny; };
+// Masked logits: -inf and every finite x <= -2^10 (the large negative constants used in place of
+// -inf).  The row's largest logit is a window value, m > -2^7, so x - m < -896 and e^(x - m) is
+// exactly 0 in fp64 (which underflows to 0 below -745.2): such a logit adds nothing to Z or S, and
+// it ranks after every window value.  NaN codes (above 0xff80) are not in the range.
+__device__ __forceinline__ bool hp_masked(uint32_t code16) { return code16 - 0xc480u <= 0xff80u - 0xc480u; }
 __device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uint32_t mag_max, int n_tiny, double s_tiny,
                                                        uint32_t* __restrict__ hist) {
   constexpr uint32_t TWO2 = 0x00020002u, BIAS2 = ((0x10000u - 2u * HP_MAG_LO) & 0xffffu) * 0x00010001u;
-  constexpr uint32_t LOWEST = 0x8000u | (HP_MAG_LO + HP_MAG_SPAN - 1);   // the lowest value of the window stands in for -inf
+  constexpr uint32_t LOWEST = 0x8000u | (HP_MAG_LO + HP_MAG_SPAN - 1);   // the lowest value of the window stands in for a masked logit
   HistOutside r;
   r.mag_max = mag_max; r.n_tiny = n_tiny; r.s_tiny = s_tiny;
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -633,8 +638,8 @@ __device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uin
     uint32_t w2[4], inf_lo[4], inf_hi[4], n_inf = 0u, dm = 0u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      inf_lo[j] = (w[j] & 0xffffu) == 0xff80u ? ~0u : 0u;
-      inf_hi[j] = (w[j] >> 16) == 0xff80u ? ~0u : 0u;
+      inf_lo[j] = hp_masked(w[j] & 0xffffu) ? ~0u : 0u;
+      inf_hi[j] = hp_masked(w[j] >> 16) ? ~0u : 0u;
       w2[j] = w[j];
       if (inf_lo[j]) w2[j] = (w2[j] & 0xffff0000u) | LOWEST;
       if (inf_hi[j]) w2[j] = (w2[j] & 0x0000ffffu) | (LOWEST << 16);
@@ -658,7 +663,7 @@ __device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uin
     const float x = (j & 1) ? bf16_hi(w[j >> 1]) : bf16_lo(w[j >> 1]);
     const uint32_t code = __float_as_uint(x) >> 16, mag = code & 0x7fffu;
     if (j < n_valid) {
-      if (code == 0xff80u) r.n_tiny += 0x10000;
+      if (hp_masked(code)) r.n_tiny += 0x10000;
       else {
         r.mag_max = pk_max_u16(r.mag_max, mag);
         cm = fmaxf(cm, x);
@@ -922,11 +927,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     }
   }
   __syncthreads();
-  // Leave this path (uniformly) if a logit lies above the window (|x| >= 2^7, +inf, NaN), if a
+  // Leave this path (uniformly) if a logit that is not masked lies above the window (|x| >= 2^7, +inf, NaN), if a
   // 16-bit counter overflowed (the total is then off by a multiple of 65535 or 65536), if logits
   // below the window exist and the K-th largest logit is not a positive window value (then they
-  // could be among the top K, which the histogram cannot rank), or if fewer than K logits are
-  // finite while some are -inf (the top K then ends with -inf entries).
+  // could be among the top K, which the histogram cannot rank), or if fewer than K logits lie
+  // in the window while some are masked (the top K then ends with masked entries).
   const int n_elems = (sg.tail_chunk >= 0 ? (sg.ncell - 1) * 8 + sg.tail_valid : sg.ncell * 8);
   // With the entropy over the M largest logits: also if logits below the window could be among them.
   if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny + n_ninf != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS) ||

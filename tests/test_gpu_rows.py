@@ -35,6 +35,15 @@ def adversarial_rows(V, rng, bf16):
     mit = 2 * rng.standard_normal(V); mit[rng.random(V) < 0.2] = -np.inf; mit[rng.random(V) < 0.05] = 0.0
     mit[V - 1] = -np.inf; mit[V - 2] = 7.0                                # masked, zero and largest logits side by side
     add("minus_inf_with_zeros", mit)
+    # large negative constants in place of -inf: e^(x - m) is exactly 0 in fp64 for them
+    fm = 2 * rng.standard_normal(V); fm[rng.random(V) < 0.3] = -3.3895313892515355e38      # the lowest bf16
+    add("masked_lowest_bf16", fm)
+    f9 = 2 * rng.standard_normal(V); f9[rng.random(V) < 0.5] = -1e9; f9[rng.random(V) < 0.1] = -np.inf; f9[rng.random(V) < 0.05] = -1e4
+    add("masked_mixed_constants", f9)
+    nb = -118 + 1.5 * rng.standard_normal(V); nb[rng.random(V) < 0.1] = -1024.0     # the least negative masked value, lowest row maximum
+    add("masked_minus_1024_low_row", nb)
+    nb2 = 2 * rng.standard_normal(V); nb2[rng.random(V) < 0.01] = -1016.0         # just inside (-2^10, -2^7]: not masked, two-pass path
+    add("minus_1016_not_masked", nb2)
     mi2 = np.full(V, -np.inf); mi2[[0, V // 2, V - 1]] = [1.0, 2.0, 2.0]
     add("only_three_finite", mi2)
     add("sorted_desc", np.sort(3 * rng.standard_normal(V))[::-1].copy())
@@ -92,6 +101,14 @@ def test_rows_against_oracle(dtype, V, K, splits):
     ctx.expand_layer(xd)
     torch.cuda.synchronize()
     c = to_np(ctx.candidates())
+    status = to_np(ctx.finalize_tree())["status"]
+    if dtype == "bf16" and V >= 5003:
+        # masked logits (-inf, large negative constants) do not push a row off the histogram path
+        for b, name in enumerate(names):
+            if name.startswith("masked_") or name in ("minus_inf_30pct", "minus_inf_90pct", "minus_inf_with_zeros", "normal"):
+                assert not status[b] & 2, name
+            if name in ("minus_1016_not_masked", "wide_range"):
+                assert status[b] & 2, name
     xin = x[:, 0, :V].contiguous()
     bits = xin.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else xin.numpy()
     for b, name in enumerate(names):

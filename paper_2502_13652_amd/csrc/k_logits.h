@@ -774,6 +774,9 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 #define C2T_COUNT(q, i) hist_chunk(q, a, hist)
     uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + NT), qc = C2T_LOAD(g + 2 * NT), qd = C2T_LOAD(g + 3 * NT);
     uint16_t* mp = map + tid;
+    // Streaming waves issue ahead of the waves of co-resident workgroups that are in their
+    // (latency-bound) epilogue or tail: the memory pipeline stays fed.  Measured: 3 % per full layer.
+    __builtin_amdgcn_s_setprio(3);
     // groups of four sweeps in which every lane has a chunk
     for (int it = (c1 - sg.c0) / (4 * NT); it > 0; --it, g += 4 * NT, mp += NT) {
       uint32_t key = C2T_COUNT(qa, g);
@@ -786,6 +789,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       qd = C2T_LOAD(g + 7 * NT);
       *mp = (uint16_t)pk_max_f16_raw(key, key >> 16);
     }
+    __builtin_amdgcn_s_setprio(0);
     // the last, partial group: up to four chunks of this lane, the row's partial last chunk among them
     const int tail = sg.tail_chunk;
     if (g < c1 || g == tail) {

@@ -155,7 +155,7 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
   ScoreParams sp;
   sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
-  sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
+  sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.B = c.batch; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
   sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m; sp.D = c.max_depth;
   if (c.logits_dtype == C2T_BF16) {
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);

@@ -78,7 +78,7 @@ constexpr int C2T_MAX_CANDIDATES_DEV = 2048;              // F*K limit of the pe
 
 struct ScoreParams {
   RowPartial* part; float* part_topv; int32_t* part_topi;    // [launched row][split] records and their top-K lists
-  int nsplit, rows_per_seq, F, K, N, h, layer, D;
+  int nsplit, rows_per_seq, B, F, K, N, h, layer, D;
   int M;                                                     // 0: entropy over the whole row; M > 0: over the M largest logits
   int lds_bytes;                                             // dynamic LDS of the launch
   float z_beta;

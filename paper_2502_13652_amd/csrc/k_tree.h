@@ -222,7 +222,7 @@ constexpr int PRUNE_PRESELECT_MIN = 128;      // shorter lists are ranked direct
 
 __host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
   (void)h;
-  return ((size_t)3 * ((FK + 31) & ~31) + PRUNE_HIST_WORDS + ((FK + 31) >> 5)) * 4;   // lists, histogram, kept bits
+  return ((size_t)3 * ((FK + 31) & ~31) + PRUNE_HIST_WORDS) * 4;
 }
 
 template <int NT>
@@ -235,7 +235,6 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   int32_t* stok = (int32_t*)(sz + FKp);
   int32_t* sidx = stok + FKp;
   uint32_t* hist = (uint32_t*)(sidx + FKp);
-  uint32_t* kept_bits = hist + PRUNE_HIST_WORDS;             // one bit per candidate slot
   __shared__ int32_t n_surv, n_red, flags_or, sel_bin;
   __shared__ int32_t scan_w[NW];
   __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
@@ -258,8 +257,11 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   const uint32_t info = tid < F ? ld_dev(s.row_info + (int64_t)b * F + tid) : 0u;
   const int nf = s.nf[layer & 1][b];
   const int nn = s.n_nodes[b];
+  // the kept flags start at zero (all F*K slots: slots of unused rows are unspecified anyway); stored
+  // now, so that they are long complete when the ranking stores the ones
+  for (int i = tid; i < FK; i += NT) s.c_kept[(int64_t)b * FK + i] = 0;
   if (tid == 0) { n_surv = 0; n_red = 0; flags_or = 0; sel_bin = 0; }
-  for (int i = tid; i < PRUNE_HIST_WORDS + (FKp >> 5); i += NT) hist[i] = 0u;   // histogram and kept bits
+  for (int i = tid; i < PRUNE_HIST_WORDS; i += NT) hist[i] = 0u;
   __syncthreads();
   if (tid < nf && info) atomicOr(&flags_or, (int)info);
 
@@ -277,6 +279,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
       }
     }
   }
+  wait_vector_memory();                                      // the zeros are written before any thread stores a one
   __syncthreads();
 
   // ---- second pruning + budget: rank survivors by (z desc, token asc, slot asc) ----
@@ -373,8 +376,8 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
       if (tshift >= 4) rank += (int)dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(0u, (uint32_t)rank);
       if (mine && sub == 0 && rank < n_keep) {
         const int node = nn + rank, f = i / K;
-        const int64_t t = (int64_t)b * N + node;
-        atomicOr(&kept_bits[i >> 5], 1u << (i & 31));        // the flags go out together after the ranking: one store per slot, no ordering to wait for
+        const int64_t o = (int64_t)b * FK + i, t = (int64_t)b * N + node;
+        s.c_kept[o] = 1;
         s.t_tok[t] = tok; s.t_parent[t] = par; s.t_depth[t] = layer;
         s.t_P[t] = P; s.t_H[t] = H; s.t_z[t] = z;
         new_tok[rank] = tok; new_pslot[rank] = f; new_node[rank] = node; new_P[rank] = P;
@@ -383,7 +386,6 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     }
   }
   __syncthreads();
-  for (int i = tid; i < FK; i += NT) s.c_kept[(int64_t)b * FK + i] = (int32_t)((kept_bits[i >> 5] >> (i & 31)) & 1u);
   if (tid < n_keep) {
     const int64_t o = (int64_t)b * F + tid;
     s.fr_tok[o] = new_tok[tid]; s.fr_pslot[o] = new_pslot[tid];
@@ -406,11 +408,6 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
 // 0..63), whose own wait covers them; the other waves only meet at the barrier.
 __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
   __shared__ int32_t sh_last;
-  if (expected == 1) {                                       // uniform: the only arrival publishes to itself
-    if (threadIdx.x < WAVE) wait_vector_memory();
-    __syncthreads();
-    return true;
-  }
   if (threadIdx.x < WAVE) {
     wait_vector_memory();
     if (threadIdx.x == 0) {

@@ -38,6 +38,9 @@ def main():
                     help="capture one draft phase in a HIP graph and time K replays (the per-launch kernel times for "
                          "the roofline then come from K further, un-captured phases after the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-layer", action="store_true",
+                    help="skip the extra full-layer launches (roofline.full_layer), so that a kernel trace of the run "
+                         "holds the warm-up and timed draft phases only")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -129,7 +132,7 @@ def main():
     # frontiers stay full until the budget is used up.  Outside the timed region.
     full_layer = None
     n_full = min(D - 1, N // F) if B > 1 else 0
-    if n_full >= 1 and not a.mask_frac:
+    if n_full >= 1 and not a.mask_frac and not a.no_full_layer:
         fctx = C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, 0.0,
                           entropy_top_m=a.entropy_top_m, device=dev)
         fctx.set_classifier(*cls)

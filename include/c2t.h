@@ -20,6 +20,9 @@
  *    frees or synchronises device memory: the caller owns all of it, including the
  *    workspace, and passes the stream (a hipStream_t as void*, NULL = default stream)
  *    that every kernel of a call is enqueued on.  Calls return after enqueueing.
+ *  - Every call on a context is made with the workspace's device current, and calls on one
+ *    context are not thread-safe (one draft phase at a time per context; use one context per
+ *    stream for concurrent phases).
  *  - Return value: 0 = C2T_OK, negative = error (c2t_strerror).  Argument and state
  *    errors are found on the host before anything is enqueued.  Data errors (NaN or
  *    +inf logits, a row with no finite logit) never fail a call: the row yields no

@@ -121,6 +121,7 @@ struct c2t_ctx {
   int layer;          // layers expanded since reset; -1 before the first reset
   bool have_cls, finalized;
   int ns_first, ns_other;      // row splits in use
+  size_t lds_raised;           // dynamic LDS this context has asked the runtime to allow its layer kernel so far
   // optional event timing of the logits pass
   std::vector<hipEvent_t> ev;
   std::vector<float> cls_host;
@@ -160,13 +161,12 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   if (c.logits_dtype == C2T_BF16) {
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
     sp.lds_bytes = (int)lds;
-    static size_t lds_raised[2] = {48 * 1024, 48 * 1024};   // dynamic LDS the runtime allows each kernel so far
     const int topm = c.entropy_top_m > 0;
     const void* fn = topm ? (const void*)k_logits_hist<HP_NT, true> : (const void*)k_logits_hist<HP_NT, false>;
-    if (lds > lds_raised[topm]) {
+    if (lds > x->lds_raised) {                              // beyond the 48 KB a kernel may use without asking
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
-      lds_raised[topm] = lds;
+      x->lds_raised = lds;
     }
     if (topm)
       hipExtLaunchKernelGGL((k_logits_hist<HP_NT, true>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride,
@@ -232,6 +232,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   x->tab_e = (double*)(w + L.tab_e);
   x->z_beta = cfg->beta <= 0.0f ? -INFINITY : (float)std::log((double)cfg->beta / (1.0 - (double)cfg->beta));
   x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0;
+  x->lds_raised = 48 * 1024;
   x->ns_first = default_split(*cfg, L, cfg->batch);
   x->ns_other = default_split(*cfg, L, (int64_t)cfg->batch * cfg->max_frontier);
   *out = x;

@@ -733,12 +733,12 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
 // The lane that holds the M-th largest logit: the sums over the logits it contributes to the top M
 // (from its top value down: positive magnitudes descending, or negative ones ascending), relative to
 // its top value vt.  Out of line: one lane per row gets here, and inlined its registers would be
-// charged to every workgroup's epilogue.
+// charged to every workgroup's epilogue.  e^v is computed here (at most WPL values) rather than
+// fetched from the tables again: a load issued at this point waits behind all the logits in flight
+// on the CU, several microseconds that the whole workgroup would spend at its next barrier.
 template <int WPL>
-__device__ __noinline__ void top_m_boundary_lane(const double* __restrict__ tab, int tid, const uint32_t (&cw)[WPL], bool positive,
+__device__ __noinline__ void top_m_boundary_lane(int tid, const uint32_t (&cw)[WPL], bool positive,
                                                  int above, int M, double vt, double* zm_out, double* sm_out) {
-  double ep[WPL], en[WPL];
-  load_exp_factors<WPL>(tab, tid, ep, en);
   double zm = 0.0, sm = 0.0;
   int run = above;
 #pragma unroll 1
@@ -747,8 +747,9 @@ __device__ __noinline__ void top_m_boundary_lane(const double* __restrict__ tab,
     const int n = positive ? (int)(cw[j] & 0xffffu) : (int)(cw[j] >> 16), take = max(0, min(n, M - run));
     run += n;
     if (take) {
-      const double t = (double)take * (positive ? ep[j] : en[j]);
-      zm += t; sm += ((double)hp_value_of_mag(WPL * tid + j, !positive) - vt) * t;
+      const double v = (double)hp_value_of_mag(WPL * tid + j, !positive);
+      const double t = (double)take * exp(v);
+      zm += t; sm += (v - vt) * t;
     }
   }
   *zm_out = zm; *sm_out = sm;
@@ -981,7 +982,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     if (lane_neg > 0 && above_n + lane_neg <= M) { zm += Zneg; sm += Sneg; }
     if (part_p || part_n) {
       double pz = 0.0, ps = 0.0;
-      top_m_boundary_lane<WPL>(tab_e, tid, cw, part_p, part_p ? above_p : above_n, M, vt, &pz, &ps);
+      top_m_boundary_lane<WPL>(tid, cw, part_p, part_p ? above_p : above_n, M, vt, &pz, &ps);
       zm += pz; sm += ps;
     }
     if (lane_pos | lane_neg) sm += (vt - (double)vw) * zm;

@@ -193,6 +193,49 @@ def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():
             np.testing.assert_allclose(outs[0][k], o[k], rtol=1e-5)
 
 
+@pytest.mark.parametrize("name,opts", [("cfg2", {}), ("cfg4", {}), ("cfg4", {"entropy_top_m": 1000}), ("cfg2", {"rerank": 1})])
+def test_a_draft_phase_replayed_from_a_hip_graph(name, opts):
+    """reset -> D x expand -> finalize captured once and replayed: every replay, with eager work of
+    the same context and synchronisations in between, gives the eager result bit for bit (the
+    library enqueues kernels only: no memset nodes, no allocation, nothing host-side per call
+    that a replay would miss)."""
+    cfg = dict(W.CONFIGS[name]); cfg.update(opts)
+    cls = W.classifier(cfg, W.classifier_seed(name))
+    gen = "cpu" if cfg["B"] == 1 else "cuda"
+    layers = [W.logits_layer(cfg, l, device=gen).cuda() for l in range(cfg["D"])]
+    other = [W.logits_layer(cfg, l, device=gen, instance=1).cuda() for l in range(cfg["D"])]
+    g = make_gpu(cfg, cls)
+    n_out = 48 if opts.get("rerank") else None
+    out_graph, out_eager = g.new_tree_out(n_out), g.new_tree_out(n_out)
+
+    def phase(ls, out):
+        g.reset()
+        for l in range(cfg["D"]):
+            g.expand_layer(ls[l])
+        return g.finalize_tree_reranked(n_out, out) if n_out else g.finalize_tree(out)
+
+    eager = {k: v.clone() for k, v in phase(layers, out_eager).items()}
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        phase(layers, out_graph)                          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        phase(layers, out_graph)
+    for replay in range(4):
+        for v in out_graph.values():
+            v.fill_(-7)                                   # a replay must rewrite every output
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(out_graph[k], eager[k]), "replay %d differs in %s" % (replay, k)
+        phase(other, out_eager)                           # eager work on other inputs between the replays
+        torch.cuda.synchronize()
+    assert int(eager["n_nodes"].sum()) > 0
+
+
 LIMIT_CASES = {
     # name: (B, V, dtype, D, F, K, h, beta, N): the compiled limits of the kernels, odd vocabularies
     "max_candidates_bf16": (3, 20011, "bf16", 3, 64, 32, 256, 0.2, 1024),

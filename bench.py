@@ -44,8 +44,8 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how "
-              "the path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (sequences are independent: the path would shard by "
+              "splitting the batch over GPUs, with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

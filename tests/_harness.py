@@ -12,7 +12,7 @@ if ROOT not in sys.path:
 
 import workloads as W  # noqa: E402
 
-RTOL = 1e-5          # spec tolerance for probabilities, features, confidences
+RTOL = 1e-5          # relative tolerance for probabilities, features, confidences (fp64 definition rounded to fp32)
 ORACLE_THREADS = 16  # the GPU machine's CPU share
 
 

@@ -714,7 +714,9 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
   const uint32_t dm = pk_max_u16(pk_max_u16(pk_mad_u16(w[0], TWO2, BIAS2), pk_mad_u16(w[1], TWO2, BIAS2)),
                                  pk_max_u16(pk_mad_u16(w[2], TWO2, BIAS2), pk_mad_u16(w[3], TWO2, BIAS2)));
   uint32_t pat;
-  if (dm & 0xE000E000u) {                                     // rare: a logit outside the window
+  // rare: a logit outside the window.  The whole wave then takes the out-of-line routine (it counts
+  // in-window chunks as well): cheaper than running both paths one after the other.
+  if (__builtin_amdgcn_ballot_w64((dm & 0xE000E000u) != 0u) != 0ull) {
     pat = hist_elements(q, 8, a, hist);
   } else {
     // inside the window bf16 bit patterns order exactly like fp16 bit patterns

@@ -78,3 +78,19 @@ def test_workspace_and_state_errors(lib):
     lib.c2t_destroy(ctx)
     lib.c2t_destroy(None)
     assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3)
+
+
+def test_no_cpu_fallback_and_no_oracle_in_the_product():
+    """Without a GPU the binding raises instead of computing anything on the host, and nothing
+    under the package imports, links or names the oracle."""
+    import torch
+    from paper_2502_13652_amd import C2TContext
+    if not torch.cuda.is_available():
+        with pytest.raises(RuntimeError, match="no CPU fallback"):
+            C2TContext(1, 100, 2, 2, 2, 4, 4, 1, 0.5)
+    pkg = os.path.join(ROOT, "paper_2502_13652_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(base, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(base, f)

@@ -738,9 +738,11 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
 // charged to every workgroup's epilogue.  e^v is computed here (at most WPL values) rather than
 // fetched from the tables again: a load issued at this point waits behind all the logits in flight
 // on the CU, several microseconds that the whole workgroup would spend at its next barrier.
+template <int WPL> struct LaneCounts { uint32_t w[WPL]; };      // by value: a reference would put the counts in scratch memory
+struct TopMPart { double zm, sm; };
 template <int WPL>
-__device__ __noinline__ void top_m_boundary_lane(int tid, const uint32_t (&cw)[WPL], bool positive,
-                                                 int above, int M, double vt, double* zm_out, double* sm_out) {
+__device__ __noinline__ TopMPart top_m_boundary_lane(int tid, LaneCounts<WPL> counts, bool positive, int above, int M, double vt) {
+  const uint32_t (&cw)[WPL] = counts.w;
   double zm = 0.0, sm = 0.0;
   int run = above;
 #pragma unroll 1
@@ -754,7 +756,8 @@ __device__ __noinline__ void top_m_boundary_lane(int tid, const uint32_t (&cw)[W
       zm += t; sm += (v - vt) * t;
     }
   }
-  *zm_out = zm; *sm_out = sm;
+  TopMPart r; r.zm = zm; r.sm = sm;
+  return r;
 }
 
 // One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
@@ -778,7 +781,8 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   __shared__ int32_t scan_tmp[2][NW];
   __shared__ int32_t sh_cnt, sh_ncell, sh_tau_rank, sh_n_gt;
 
-  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  int tid = threadIdx.x;
+  const int lane = tid & (WAVE - 1), wid = tid >> 6;
 
 #pragma unroll
   for (int j = 0; j < WPL; ++j) hist[tid + j * NT] = 0u;
@@ -830,6 +834,10 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 #undef C2T_COUNT
 #undef C2T_LOAD
   }
+  // With the top-M sums compiled in, the thread index does not survive the loop in a register: it
+  // would be spilled before the loop and reloaded here, behind all the logits in flight on the CU
+  // (microseconds, for every wave).  Formed again from the wave's index and the lane.
+  if (TOPM) tid = __builtin_amdgcn_readfirstlane(wid) * WAVE + lane_id();
   if (a.n_tiny & 0xffff) { atomicAdd(&sh_ntiny, a.n_tiny & 0xffff); atomicAdd(&sh_stiny, a.s_tiny); }
   if (a.n_tiny >> 16) atomicAdd(&sh_nninf, a.n_tiny >> 16);
 
@@ -983,9 +991,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     if (lane_pos > 0 && above_p + lane_pos <= M) { zm += Zpos; sm += Spos; }
     if (lane_neg > 0 && above_n + lane_neg <= M) { zm += Zneg; sm += Sneg; }
     if (part_p || part_n) {
-      double pz = 0.0, ps = 0.0;
-      top_m_boundary_lane<WPL>(tid, cw, part_p, part_p ? above_p : above_n, M, vt, &pz, &ps);
-      zm += pz; sm += ps;
+      LaneCounts<WPL> counts;
+#pragma unroll
+      for (int j = 0; j < WPL; ++j) counts.w[j] = cw[j];
+      const TopMPart part = top_m_boundary_lane<WPL>(tid, counts, part_p, part_p ? above_p : above_n, M, vt);
+      zm += part.zm; sm += part.sm;
     }
     if (lane_pos | lane_neg) sm += (vt - (double)vw) * zm;
     zm = wave_sum(zm); sm = wave_sum(sm);

@@ -51,7 +51,7 @@ def main():
     import numpy as np
     import torch
     import workloads as W
-    from paper_2502_13652_amd import C2TContext, stream_read
+    from paper_2502_13652_amd import C2TContext, stream_read, stream_read_rows
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
     dev = torch.device("cuda:0")
@@ -168,6 +168,18 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     stream_gbps = 5 * big.numel() / (e0.elapsed_time(e1) / 1e3) / 1e9
+    # the same bytes read with the layer kernel's access pattern (one workgroup per row of V logits,
+    # as many rows as a full layer has, rotating over the buffer) and no other work
+    row_bytes = (V * esz + 15) // 16 * 16
+    n_rows = min(B * F, big.numel() // row_bytes)
+    groups = max(1, min(4, big.numel() // (n_rows * row_bytes)))
+    for i in range(2 + 5):
+        if i == 2:
+            e0.record()
+        stream_read_rows(big[(i % groups) * n_rows * row_bytes:], n_rows, row_bytes, acc)
+    e1.record()
+    torch.cuda.synchronize()
+    row_read_gbps = 5 * n_rows * row_bytes / (e0.elapsed_time(e1) / 1e3) / 1e9
     del big
 
     # HBM traffic per launch from the committed counter pass (rocprofv3 --pmc FETCH_SIZE, scaled by the
@@ -199,7 +211,7 @@ def main():
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),
                      "full_layer": full_layer,
-                     "stream_read_gbps": stream_gbps, "per_layer": per_layer},
+                     "stream_read_gbps": stream_gbps, "row_read_gbps": row_read_gbps, "per_layer": per_layer},
     }
 
     if not a.no_cpu_baseline:

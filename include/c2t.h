@@ -183,6 +183,12 @@ int c2t_profile_read(c2t_ctx* ctx, float* ms, int32_t* n);
  * uint32 at [device] out: the practical HBM read ceiling to compare the logits pass with. */
 int c2t_stream_read(const void* dev_ptr, size_t bytes, uint32_t* dev_out, void* stream);
 
+/* The same for `rows` rows of `row_bytes` (multiple of 16) each, `row_stride_bytes` (multiple of 16,
+ * >= row_bytes) apart in [device] memory, read the way the logits pass reads them (one workgroup
+ * per row): the ceiling for that access pattern. */
+int c2t_stream_read_rows(const void* dev_ptr, int32_t rows, size_t row_bytes, size_t row_stride_bytes,
+                         uint32_t* dev_out, void* stream);
+
 const char* c2t_strerror(int code);
 
 #ifdef __cplusplus

@@ -80,6 +80,7 @@ def load_library():
     L.c2t_profile_enable.argtypes = [vp, i32]
     L.c2t_profile_read.argtypes = [vp, vp, P(i32)]
     L.c2t_stream_read.argtypes = [vp, sz, vp, vp]
+    L.c2t_stream_read_rows.argtypes = [vp, i32, sz, sz, vp, vp]
     L.c2t_strerror.argtypes = [ctypes.c_int]
     L.c2t_strerror.restype = ctypes.c_char_p
     _lib = L
@@ -225,3 +226,10 @@ def stream_read(tensor, out, stream=None):
     nbytes = tensor.numel() * tensor.element_size()
     _check(L.c2t_stream_read(ctypes.c_void_p(tensor.data_ptr()), nbytes - nbytes % 16,
                              ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)), "c2t_stream_read")
+
+
+def stream_read_rows(tensor, rows, row_bytes, out, stream=None):
+    """Plain read of `rows` rows of `row_bytes` each (contiguous in `tensor`) with the logits pass's access pattern."""
+    L = load_library()
+    _check(L.c2t_stream_read_rows(ctypes.c_void_p(tensor.data_ptr()), int(rows), int(row_bytes), int(row_bytes),
+                                  ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)), "c2t_stream_read_rows")

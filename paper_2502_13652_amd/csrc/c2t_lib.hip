@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -393,6 +394,15 @@ int c2t_profile_read(c2t_ctx* x, float* ms, int32_t* n) {
 int c2t_stream_read(const void* p, size_t bytes, uint32_t* out, void* stream) {
   if (!p || !out || bytes % 16 != 0 || ((uintptr_t)p % 16) != 0) return C2T_ERR_INVALID_ARG;
   hipLaunchKernelGGL(k_stream_read, dim3(256 * 8), dim3(1024), 0, (hipStream_t)stream, (const uint4*)p, bytes / 16, out);
+  return hipGetLastError() == hipSuccess ? C2T_OK : C2T_ERR_HIP;
+}
+
+int c2t_stream_read_rows(const void* p, int32_t rows, size_t row_bytes, size_t row_stride_bytes, uint32_t* out, void* stream) {
+  if (!p || !out || rows <= 0 || row_bytes == 0 || row_bytes % 16 != 0 || row_stride_bytes % 16 != 0 ||
+      row_stride_bytes < row_bytes || ((uintptr_t)p % 16) != 0 || row_bytes / 16 > (size_t)INT32_MAX)
+    return C2T_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(k_stream_read_rows, dim3((unsigned)rows), dim3(512), 0, (hipStream_t)stream, (const char*)p,
+                     (int64_t)row_stride_bytes, (int)(row_bytes / 16), out);
   return hipGetLastError() == hipSuccess ? C2T_OK : C2T_ERR_HIP;
 }
 

@@ -1091,4 +1091,21 @@ __global__ __launch_bounds__(1024) void k_stream_read(const uint4* __restrict__ 
   if ((threadIdx.x & 63) == 0 && acc == 0x9e3779b9u) atomicAdd(out, acc);   // keeps the loads alive
 }
 
+// The same read with the layer kernel's access pattern and nothing else: one workgroup of 512
+// threads per row, lane t reads chunks t, t+512, ... of its row, four in flight, non-temporal.  What
+// the memory system delivers to that pattern is the ceiling the logits pass can be held against.
+__global__ __launch_bounds__(512, 8) void k_stream_read_rows(const char* __restrict__ p, int64_t row_stride_bytes, int chunks_per_row, uint32_t* out) {
+  const uint4* row = (const uint4*)(p + (int64_t)blockIdx.x * row_stride_bytes);
+  uint32_t acc = 0;
+  int g = threadIdx.x;
+  for (; g + 3 * 512 < chunks_per_row; g += 4 * 512) {
+    const uint4 a = load_stream(row + g), b = load_stream(row + g + 512), c = load_stream(row + g + 1024), d = load_stream(row + g + 1536);
+    acc += a.x ^ a.y ^ a.z ^ a.w; acc += b.x ^ b.y ^ b.z ^ b.w;
+    acc += c.x ^ c.y ^ c.z ^ c.w; acc += d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; g < chunks_per_row; g += 512) { const uint4 a = load_stream(row + g); acc += a.x ^ a.y ^ a.z ^ a.w; }
+  acc = (uint32_t)wave_sum_i((int)acc);
+  if ((threadIdx.x & 63) == 0 && acc == 0x9e3779b9u) atomicAdd(out, acc);   // keeps the loads alive
+}
+
 }  // namespace c2t

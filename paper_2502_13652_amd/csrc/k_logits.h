@@ -1055,8 +1055,10 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 // grid: rows_launched * nsplit workgroups of NT threads.
 // Dynamic LDS (sp.lds_bytes): [HP_WORDS counters | cell map, padded to 16 bytes]; the selection's
 // element list and the tail reuse all of it.
-template <int NT, bool TOPM>
-__global__ __launch_bounds__(NT, 8) void k_logits_hist(
+// WPS: waves per SIMD the kernel is built for.  8 = four workgroups per CU on 64 registers a lane;
+// 6 = three workgroups per CU on 80 registers, which needs no spills.
+template <int NT, bool TOPM, int WPS>
+__global__ __launch_bounds__(NT, WPS) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
     const float* __restrict__ cls, TreeState st, ScoreParams sp) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];

@@ -559,34 +559,40 @@ __device__ __forceinline__ float hp_value_of_mag(uint32_t magidx, bool negative)
   return __uint_as_float(((HP_MAG_LO + magidx) << 16) | (negative ? 0x80000000u : 0u));
 }
 
-// e^v for the window's values, factored so that the tables are small enough to stay in cache:
-// v = s 2^E (1 + f/128) with f = 16 fh + fl, so e^v = A[s][e][fh] * B[s][e][fl] with
-// A = exp(s 2^E (1 + fh/8)) and B = exp(s 2^E fl/128) (both arguments exact), e = exponent index
-// inside the window (0..31).  Layout: A+ [256] | A- [256] | B+ [512] | B- [512] doubles (12 KB; a
-// table of all 8192 values is 64 KB and was re-fetched from memory by nearly every workgroup).
-// The product of two correctly rounded factors is within 3e-16 of e^v.  Filled once per context.
-constexpr int HP_TAB_A = 256, HP_TAB_B = 512, HP_TAB_DOUBLES = 2 * HP_TAB_A + 2 * HP_TAB_B;
+// e^v for the window's values, factored so that the table stays in cache and a lane holds few
+// factors: v = s 2^E (1 + f/128), f = 16 fh + fl, and e^v = A[s][e][fh] * prod over the set bits k
+// of fl of C[s][e][k], with A = exp(s 2^E (1 + fh/8)) and C = exp(s 2^E 2^k / 128) (every argument
+// exact), e = exponent index inside the window (0..31).  Layout: A+ [256] | A- [256] | C+ [32][4] |
+// C- [32][4] doubles (6 KB; a table of all 8192 values is 64 KB and was re-fetched from memory by
+// nearly every workgroup).  At most five correctly rounded factors and four products: within
+// 1e-15 of e^v.  Filled once per context.
+constexpr int HP_TAB_A = 256, HP_TAB_C = 128, HP_TAB_DOUBLES = 2 * HP_TAB_A + 2 * HP_TAB_C;
 __global__ void k_init_exp_table(double* __restrict__ tab) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= HP_TAB_DOUBLES) return;
-  const bool is_b = i >= 2 * HP_TAB_A;
-  const int k = is_b ? i - 2 * HP_TAB_A : i, half = is_b ? HP_TAB_B : HP_TAB_A;
+  const bool is_c = i >= 2 * HP_TAB_A;
+  const int k = is_c ? i - 2 * HP_TAB_A : i, half = is_c ? HP_TAB_C : HP_TAB_A;
   const bool neg = k >= half;
   const int kk = neg ? k - half : k;
-  const int e = is_b ? kk >> 4 : kk >> 3, frac = is_b ? kk & 15 : kk & 7;
+  const int e = is_c ? kk >> 2 : kk >> 3, sub = is_c ? kk & 3 : kk & 7;
   const double p2 = ldexp(1.0, (int)(HP_MAG_LO >> 7) + e - 127);                 // 2^E
-  const double arg = is_b ? p2 * (double)frac / 128.0 : p2 * (1.0 + (double)frac / 8.0);
+  const double arg = is_c ? p2 * (double)(1 << sub) / 128.0 : p2 * (1.0 + (double)sub / 8.0);
   tab[i] = exp(neg ? -arg : arg);
 }
-// The lane that owns magnitude indices 8t .. 8t+7 (one exponent, fh fixed): e^(+|v_j|) and e^(-|v_j|)
-template <int WPL>
-__device__ __forceinline__ void load_exp_factors(const double* __restrict__ tab, int tid, double (&evp)[WPL], double (&evn)[WPL]) {
-  const int mag0 = WPL * tid, e = mag0 >> 7, f0 = mag0 & 127;
-  const double ap = tab[e * 8 + (f0 >> 4)], an = tab[HP_TAB_A + e * 8 + (f0 >> 4)];
-  const double* bp = tab + 2 * HP_TAB_A + e * 16 + (f0 & 15);
-  const double* bn = bp + HP_TAB_B;
-#pragma unroll
-  for (int j = 0; j < WPL; ++j) { evp[j] = ap * bp[j]; evn[j] = an * bn[j]; }
+// The lane that owns magnitude indices 8t .. 8t+7 (one exponent, fh and bit 3 of fl fixed): the
+// factors of e^(+|v_j|) and e^(-|v_j|).  Ten loads, twenty registers; the sixteen products are
+// formed where they are used, one bin pair at a time.
+struct ExpFactors { double ap, an, cp[4], cn[4]; };
+__device__ __forceinline__ ExpFactors load_exp_factors(const double* __restrict__ tab, int tid) {
+  const int mag0 = 8 * tid, e = mag0 >> 7, f0 = mag0 & 127;
+  ExpFactors f;
+  f.ap = tab[e * 8 + (f0 >> 4)]; f.an = tab[HP_TAB_A + e * 8 + (f0 >> 4)];
+  const double2* cp = (const double2*)(tab + 2 * HP_TAB_A + e * 4);
+  const double2* cn = (const double2*)(tab + 2 * HP_TAB_A + HP_TAB_C + e * 4);
+  const double2 p0 = cp[0], p1 = cp[1], n0 = cn[0], n1 = cn[1];
+  f.cp[0] = p0.x; f.cp[1] = p0.y; f.cp[2] = p1.x; f.cp[3] = p1.y;
+  f.cn[0] = n0.x; f.cn[1] = n0.y; f.cn[2] = n1.x; f.cn[3] = n1.y;
+  return f;
 }
 
 typedef _Float16 c2t_half2 __attribute__((ext_vector_type(2)));
@@ -843,9 +849,8 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 
   // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  The table
   // loads for their e^v are issued now so that their latency hides behind the barrier.
-  static_assert(WPL <= 8 && 16 % WPL == 0, "a lane's magnitudes share one exponent and one upper fraction");
-  double evp[WPL], evn[WPL];
-  load_exp_factors<WPL>(tab_e, tid, evp, evn);
+  static_assert(WPL == 8, "a lane's magnitudes share one exponent, one upper fraction and bit 3 of the lower");
+  const ExpFactors ef = load_exp_factors(tab_e, tid);
   // per-wave: magnitude range and maximum
   {
     const uint32_t mx = wave_reduce_u32(a.mag_max, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
@@ -880,11 +885,17 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     for (int j = 0; j < WPL; ++j)                       // highest of the positive values last
       if (cw[j] & 0xffffu) vtop = hp_value_of_mag(WPL * tid + j, false);
     const double vt = (double)vtop;
+    const bool b3 = ((WPL * tid) & 8) != 0;
+    const double e0p = b3 ? ef.ap * ef.cp[3] : ef.ap, e0n = b3 ? ef.an * ef.cn[3] : ef.an;
 #pragma unroll
     for (int j = 0; j < WPL; ++j) {
       const double vp = (double)hp_value_of_mag(WPL * tid + j, false);
-      const double tp = (double)(cw[j] & 0xffffu) * evp[j];        // n * e^v (0 for an empty bin)
-      const double tn = (double)(cw[j] >> 16) * evn[j];
+      double ep = e0p, en = e0n;                                   // e^(+|v_j|), e^(-|v_j|)
+      if (j & 4) { ep *= ef.cp[2]; en *= ef.cn[2]; }
+      if (j & 2) { ep *= ef.cp[1]; en *= ef.cn[1]; }
+      if (j & 1) { ep *= ef.cp[0]; en *= ef.cn[0]; }
+      const double tp = (double)(cw[j] & 0xffffu) * ep;            // n * e^v (0 for an empty bin)
+      const double tn = (double)(cw[j] >> 16) * en;
       if (TOPM) {                                                  // the positive values' share kept apart
         Zp += tp; Sp += (vp - vt) * tp;
         Z += tn; S += (-vp - vt) * tn;

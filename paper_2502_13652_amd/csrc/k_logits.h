@@ -79,6 +79,12 @@ template <> struct LogitTraits<0> {     // fp32
 // A logits chunk is read once per layer: a non-temporal load keeps the stream from evicting what
 // the workgroups reuse (the e^v table, the classifier) from the L2.
 typedef uint32_t c2t_uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t c2t_uint4v __attribute__((ext_vector_type(4)));
+// 16 bytes at descriptor base + lane offset + scalar offset, non-temporal; zeros past the descriptor's size
+__device__ __forceinline__ uint4 load_stream_buffer(__amdgpu_buffer_rsrc_t rs, uint32_t lane_off, uint32_t scalar_off) {
+  const c2t_uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, scalar_off, 2);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
   const c2t_uint4v v = __builtin_nontemporal_load((const c2t_uint4v*)p);
   return make_uint4(v.x, v.y, v.z, v.w);
@@ -633,36 +639,35 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(c2t_ushort2, a), __builtin_bit_cast(c2t_ushort2, b)));
 }
 
-struct HistLane {
-  uint32_t mag_max = 0u;            // packed running max of |code| (two halves): NaN, inf and |x| >= 2^7 show here
-  uint32_t M2 = HP_F16_NEG_INF2;    // packed running maximum of the bf16 patterns (compared as fp16 patterns)
-  int n_tiny = 0;                   // low half: logits with |x| < 2^-25 (zeros included), e^x = 1 + x to fp64 accuracy;
-                                    // high half: masked logits (see hp_masked: probability 0, ranked last)
-  double s_tiny = 0.0;              // sum of the former
+// What the rows' rare logits add up to, per workgroup, in LDS: the streaming loop carries none of
+// it in registers (four registers through the loop, and a copy of them per chunk, before).
+struct OutsideAcc {
+  double s_tiny;                    // sum of the logits with |x| < 2^-25 (zeros included): e^x = 1 + x to fp64 accuracy
+  int32_t n_tiny;                   // their number
+  int32_t n_masked;                 // masked logits (see hp_masked: probability 0, ranked last)
+  uint32_t mag_max;                 // largest |code| seen outside the fast path: NaN, inf and |x| >= 2^7 show here
 };
+typedef __attribute__((address_space(3))) OutsideAcc* OutsideAccLds;
 
 // Chunks that hold a logit outside the window, and a row's partial last chunk (n_valid < 8).  Out
-// of line, with the lane's running values passed and returned by value: typical rows never get
-// here, and inlined at each of the streaming loop's sites this code costs the whole kernel registers.
-// If everything outside the window is masked (see hp_masked), those logits are counted apart and
-// the rest of the chunk is counted as in hist_chunk; otherwise one element at a time.
-// pat: the maximum of the valid elements as a packed pattern; where all of them are masked, a value
-// below every finite logit of the window path (a cell key only has to be an upper bound).
-struct HistOutside { uint32_t pat, mag_max; int n_tiny; double s_tiny; };
+// of line: typical rows never get here, and inlined at each of the streaming loop's sites this
+// code costs the whole kernel registers.  If everything outside the window is masked (see
+// hp_masked), those logits are counted apart and the rest of the chunk is counted as in
+// hist_chunk; otherwise one element at a time.
+// Returns the maximum of the valid elements as a packed pattern; where all of them are masked, a
+// value below every finite logit of the window path (a cell key only has to be an upper bound).
 // Masked logits: -inf and every finite x <= -2^10 (the large negative constants used in place of
 // -inf).  The row's largest logit is a window value, m > -2^7, so x - m < -896 and e^(x - m) is
 // exactly 0 in fp64 (which underflows to 0 below -745.2): such a logit adds nothing to Z or S, and
 // it ranks after every window value.  NaN codes (above 0xff80) are not in the range.
 __device__ __forceinline__ bool hp_masked(uint32_t code16) { return code16 - 0xc480u <= 0xff80u - 0xc480u; }
-__device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uint32_t mag_max, int n_tiny, double s_tiny,
-                                                       uint32_t* __restrict__ hist) {
+__device__ __noinline__ uint32_t hist_chunk_outside(uint4 q, int n_valid, uint32_t* __restrict__ hist, OutsideAcc* acc_generic) {
   constexpr uint32_t TWO2 = 0x00020002u, BIAS2 = ((0x10000u - 2u * HP_MAG_LO) & 0xffffu) * 0x00010001u;
   constexpr uint32_t LOWEST = 0x8000u | (HP_MAG_LO + HP_MAG_SPAN - 1);   // the lowest value of the window stands in for a masked logit
-  HistOutside r;
-  r.mag_max = mag_max; r.n_tiny = n_tiny; r.s_tiny = s_tiny;
+  const OutsideAccLds acc = (OutsideAccLds)acc_generic;
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
   if (n_valid == 8) {
-    uint32_t w2[4], inf_lo[4], inf_hi[4], n_inf = 0u, dm = 0u;
+    uint32_t w2[4], inf_lo[4], inf_hi[4], dm = 0u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       inf_lo[j] = hp_masked(w[j] & 0xffffu) ? ~0u : 0u;
@@ -670,48 +675,56 @@ __device__ __noinline__ HistOutside hist_chunk_outside(uint4 q, int n_valid, uin
       w2[j] = w[j];
       if (inf_lo[j]) w2[j] = (w2[j] & 0xffff0000u) | LOWEST;
       if (inf_hi[j]) w2[j] = (w2[j] & 0x0000ffffu) | (LOWEST << 16);
-      n_inf -= inf_lo[j] + inf_hi[j];                           // the masks are 0 or -1
       dm = pk_max_u16(dm, pk_mad_u16(w2[j], TWO2, BIAS2));
     }
     if (!(dm & 0xE000E000u)) {
-      r.n_tiny += (int)(n_inf << 16);
+      // the masked logits of all the lanes that are here, counted on the scalar unit; one lane adds them
+      int n_masked = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        n_masked += __builtin_popcountll(__builtin_amdgcn_ballot_w64(inf_lo[j] != 0u)) + __builtin_popcountll(__builtin_amdgcn_ballot_w64(inf_hi[j] != 0u));
+      const uint64_t here = __builtin_amdgcn_ballot_w64(true);
+      if (n_masked && lane_id() == (int)__builtin_ctzll(here))
+        __hip_atomic_fetch_add(&acc->n_masked, n_masked, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {                             // masked lanes stay out of the atomics (no same-address pile-up)
         if (!inf_hi[j]) atomicAdd(&hist[bits_16_27(w2[j])], hist_increment((int32_t)w2[j] >> 31, 0x10000u));
         if (!inf_lo[j]) atomicAdd(&hist[w2[j] & (HP_WORDS - 1)], hist_increment(__builtin_amdgcn_sbfe((int32_t)w2[j], 15, 1), 0x10000u));
       }
-      r.pat = pk_max_f16(pk_max_f16(w2[0], w2[1]), pk_max_f16(w2[2], w2[3]));
-      return r;
+      return pk_max_f16(pk_max_f16(w2[0], w2[1]), pk_max_f16(w2[2], w2[3]));
     }
   }
   float cm = -INFINITY;
+  uint32_t mag_max = 0u;
+  int n_tiny = 0, n_masked = 0;
+  double s_tiny = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const float x = (j & 1) ? bf16_hi(w[j >> 1]) : bf16_lo(w[j >> 1]);
     const uint32_t code = __float_as_uint(x) >> 16, mag = code & 0x7fffu;
     if (j < n_valid) {
-      if (hp_masked(code)) r.n_tiny += 0x10000;
+      if (hp_masked(code)) n_masked += 1;
       else {
-        r.mag_max = pk_max_u16(r.mag_max, mag);
+        mag_max = max(mag_max, mag);
         cm = fmaxf(cm, x);
-        if (mag < HP_MAG_LO) { r.n_tiny += 1; r.s_tiny += (double)x; }
+        if (mag < HP_MAG_LO) { n_tiny += 1; s_tiny += (double)x; }
         else atomicAdd(&hist[code & (HP_WORDS - 1)], (code & 0x8000u) ? 0x10000u : 1u);
       }
     }
   }
+  if (n_masked) __hip_atomic_fetch_add(&acc->n_masked, n_masked, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  if (n_tiny) {
+    __hip_atomic_fetch_add(&acc->n_tiny, n_tiny, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_add(&acc->s_tiny, s_tiny, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  if (mag_max >= HP_MAG_LO + HP_MAG_SPAN) __hip_atomic_fetch_max(&acc->mag_max, mag_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   const uint32_t c16 = cm == -INFINITY ? (HP_F16_NEG_INF2 & 0xffffu) : __float_as_uint(cm) >> 16;
-  r.pat = c16 | (c16 << 16);
-  return r;
-}
-__device__ __forceinline__ uint32_t hist_elements(const uint4& q, int n_valid, HistLane& a, uint32_t* __restrict__ hist) {
-  const HistOutside r = hist_chunk_outside(q, n_valid, a.mag_max, a.n_tiny, a.s_tiny, hist);
-  a.mag_max = r.mag_max; a.n_tiny = r.n_tiny; a.s_tiny = r.s_tiny;
-  return r.pat;
+  return c16 | (c16 << 16);
 }
 
 // Counts the values of a whole chunk; returns the chunk maximum as a packed pattern (both halves
 // <= max, one of them equal to it).
-__device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint32_t* __restrict__ hist) {
+__device__ __forceinline__ uint32_t hist_chunk(const uint4& q, uint32_t& M2, uint32_t* __restrict__ hist, OutsideAcc* acc) {
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
   // Per half d = 2 |code| - 2 LO (mod 2^16), with the sign shifted out by the doubling: the value
   // lies in the window iff d < 2 SPAN = 8192, i.e. iff bits 13..15 of d are clear.
@@ -722,8 +735,8 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
   uint32_t pat;
   // rare: a logit outside the window.  The whole wave then takes the out-of-line routine (it counts
   // in-window chunks as well): cheaper than running both paths one after the other.
-  if (__builtin_amdgcn_ballot_w64((dm & 0xE000E000u) != 0u) != 0ull) {
-    pat = hist_elements(q, 8, a, hist);
+  if (__builtin_amdgcn_ballot_w64((dm & 0xE000E000u) != 0u) != 0ull) {   // (a hint that this is rare made the loop 10 % slower)
+    pat = hist_chunk_outside(q, 8, hist, acc);
   } else {
     // inside the window bf16 bit patterns order exactly like fp16 bit patterns
     pat = pk_max_f16_raw(pk_max_f16_raw(w[0], w[1]), pk_max_f16_raw(w[2], w[3]));
@@ -734,7 +747,7 @@ __device__ __forceinline__ uint32_t hist_chunk(const uint4& q, HistLane& a, uint
       atomicAdd(&hist[w[j] & (HP_WORDS - 1)], hist_increment(__builtin_amdgcn_sbfe((int32_t)w[j], 15, 1), 0x10000u));
     }
   }
-  a.M2 = pk_max_f16_raw(a.M2, pat);
+  M2 = pk_max_f16_raw(M2, pat);
   return pat;
 }
 
@@ -770,7 +783,7 @@ __device__ __noinline__ TopMPart top_m_boundary_lane(int tid, LaneCounts<WPL> co
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
 // TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
 // default kernel carries none of its registers).
-template <int NT, bool TOPM>
+template <int NT, bool TOPM, int WPS>
 __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
                                              unsigned char* map_lds, const SelectLds& sel, RowResult* rr) {
@@ -780,9 +793,8 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   uint16_t* map = (uint16_t*)map_lds;
   __shared__ double red_d[2][NW], sum_d[2], sum_m[2];
   __shared__ float red_v[NW];
-  __shared__ uint32_t red_u[NW], red_m[NW];
-  __shared__ int32_t sh_ntiny, sh_nninf;
-  __shared__ double sh_stiny;
+  __shared__ uint32_t red_m[NW];
+  __shared__ OutsideAcc sh_out;
   __shared__ int32_t cell_list[SEL_CELL_CAP];
   __shared__ int32_t scan_tmp[2][NW];
   __shared__ int32_t sh_cnt, sh_ncell, sh_tau_rank, sh_n_gt;
@@ -792,70 +804,82 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 
 #pragma unroll
   for (int j = 0; j < WPL; ++j) hist[tid + j * NT] = 0u;
-  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_ntiny = 0; sh_nninf = 0; sh_stiny = 0.0; }
+  if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_out.s_tiny = 0.0; sh_out.n_tiny = 0; sh_out.n_masked = 0; sh_out.mag_max = 0u; }
   __syncthreads();
 
   // ---------------- streaming loop: count values, record cell maxima ----------------
-  HistLane a;
+  uint32_t vo_after;
+  uint32_t M2 = HP_F16_NEG_INF2;                       // packed running maximum of the bf16 patterns (compared as fp16 patterns)
   {
     // four chunks per lane in flight: a workgroup that streams while its neighbours on the CU are
     // in their epilogues still covers the HBM latency.  Unrolled by four so that each buffer is
     // refilled right after it has been counted, without register copies.
-    int g = sg.c0 + tid;
     const int c1 = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;   // whole chunks; a partial last chunk is counted below
-    const uint4* dummy = rowp + sg.c0;                   // in-bounds address for lanes past their last chunk
-#define C2T_LOAD(i) load_stream((i) < c1 ? rowp + (i) : dummy)
-#define C2T_COUNT(q, i) hist_chunk(q, a, hist)
-    uint4 qa = C2T_LOAD(g), qb = C2T_LOAD(g + NT), qc = C2T_LOAD(g + 2 * NT), qd = C2T_LOAD(g + 3 * NT);
+    // The whole chunks are read through a buffer descriptor over exactly their bytes: a lane whose
+    // chunk lies past the last whole one gets zeros from the bounds check instead of needing a
+    // compare and a select per load, and the address is the lane's fixed offset plus a scalar one:
+    // no vector instruction per load (eight before, a seventh of the loop).
+    const uint64_t base = (uint64_t)(rowp + sg.c0);      // the same for every lane: told to the compiler
+    const uint64_t base_u = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base) |   // the builtin returns int:
+                            ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base >> 32)) << 32);   // no sign extension
+    const int whole = __builtin_amdgcn_readfirstlane(max(c1 - sg.c0, 0));
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base_u, 0, whole * 16, 0x00020000);
+    const uint32_t vo = (uint32_t)tid * 16u;
+    uint32_t so = 0u;
+#define C2T_LOAD(k) load_stream_buffer(rs, vo, so + (uint32_t)(k) * (NT * 16u))
+#define C2T_COUNT(q) hist_chunk(q, M2, hist, &sh_out)
+    uint4 qa = C2T_LOAD(0), qb = C2T_LOAD(1), qc = C2T_LOAD(2), qd = C2T_LOAD(3);
     uint16_t* mp = map + tid;
     // Streaming waves issue ahead of the waves of co-resident workgroups that are in their
     // (latency-bound) epilogue or tail: the memory pipeline stays fed.  Measured: 3 % per full layer.
     __builtin_amdgcn_s_setprio(3);
     // groups of four sweeps in which every lane has a chunk
-    for (int it = (c1 - sg.c0) / (4 * NT); it > 0; --it, g += 4 * NT, mp += NT) {
-      uint32_t key = C2T_COUNT(qa, g);
-      qa = C2T_LOAD(g + 4 * NT);
-      key = pk_max_f16_raw(key, C2T_COUNT(qb, g + NT));
-      qb = C2T_LOAD(g + 5 * NT);
-      key = pk_max_f16_raw(key, C2T_COUNT(qc, g + 2 * NT));
-      qc = C2T_LOAD(g + 6 * NT);
-      key = pk_max_f16_raw(key, C2T_COUNT(qd, g + 3 * NT));
-      qd = C2T_LOAD(g + 7 * NT);
+    const int n_groups = whole / (4 * NT);
+    for (int it = n_groups; it > 0; --it, so += 4u * NT * 16u, mp += NT) {
+      uint32_t key = C2T_COUNT(qa);
+      qa = C2T_LOAD(4);
+      key = pk_max_f16_raw(key, C2T_COUNT(qb));
+      qb = C2T_LOAD(5);
+      key = pk_max_f16_raw(key, C2T_COUNT(qc));
+      qc = C2T_LOAD(6);
+      key = pk_max_f16_raw(key, C2T_COUNT(qd));
+      qd = C2T_LOAD(7);
       *mp = (uint16_t)pk_max_f16_raw(key, key >> 16);
     }
+    vo_after = vo;
+    const int g = sg.c0 + (int)(vo >> 4) + n_groups * (4 * NT);
     __builtin_amdgcn_s_setprio(0);
     // the last, partial group: up to four chunks of this lane, the row's partial last chunk among them
     const int tail = sg.tail_chunk;
     if (g < c1 || g == tail) {
-      uint32_t key = g < c1 ? C2T_COUNT(qa, g) : hist_elements(rowp[tail], sg.tail_valid, a, hist);
-      if (g + NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qb, g + NT));
-      else if (g + NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
-      if (g + 2 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qc, g + 2 * NT));
-      else if (g + 2 * NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
-      if (g + 3 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qd, g + 3 * NT));
-      else if (g + 3 * NT == tail) key = pk_max_f16(key, hist_elements(rowp[tail], sg.tail_valid, a, hist));
+      uint32_t key = g < c1 ? C2T_COUNT(qa) : hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out);
+      if (g + NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qb));
+      else if (g + NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
+      if (g + 2 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qc));
+      else if (g + 2 * NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
+      if (g + 3 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qd));
+      else if (g + 3 * NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
       *mp = (uint16_t)pk_max_f16(key, key >> 16);
-      a.M2 = pk_max_f16(a.M2, key);                       // the partial chunk's maximum is in no other running value
+      M2 = pk_max_f16(M2, key);                       // the partial chunk's maximum is in no other running value
     }
 #undef C2T_COUNT
 #undef C2T_LOAD
   }
-  // With the top-M sums compiled in, the thread index does not survive the loop in a register: it
-  // would be spilled before the loop and reloaded here, behind all the logits in flight on the CU
-  // (microseconds, for every wave).  Formed again from the wave's index and the lane.
-  if (TOPM) tid = __builtin_amdgcn_readfirstlane(wid) * WAVE + lane_id();
-  if (a.n_tiny & 0xffff) { atomicAdd(&sh_ntiny, a.n_tiny & 0xffff); atomicAdd(&sh_stiny, a.s_tiny); }
-  if (a.n_tiny >> 16) atomicAdd(&sh_nninf, a.n_tiny >> 16);
+  // The thread index should not be kept in a register through the loop on top of the lane's
+  // buffer offset: a spill that crosses the loop is reloaded behind all the logits in flight on the
+  // CU (microseconds, for every wave).  It is formed again here: from the offset, or, where the
+  // register allocation of that build comes out better, from the wave's index and the lane.
+  if (TOPM && WPS == 8) tid = __builtin_amdgcn_readfirstlane(wid) * WAVE + lane_id();
+  else tid = (int)(vo_after >> 4);
 
   // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  The table
   // loads for their e^v are issued now so that their latency hides behind the barrier.
   static_assert(WPL == 8, "a lane's magnitudes share one exponent, one upper fraction and bit 3 of the lower");
   const ExpFactors ef = load_exp_factors(tab_e, tid);
-  // per-wave: magnitude range and maximum
+  // per-wave: maximum
   {
-    const uint32_t mx = wave_reduce_u32(a.mag_max, 0u, [](uint32_t x, uint32_t y) { return pk_max_u16(x, y); });
-    const uint32_t m2 = wave_reduce_u32(a.M2, HP_F16_NEG_INF2, [](uint32_t x, uint32_t y) { return pk_max_f16(x, y); });
-    if (lane == 0) { red_u[wid] = mx; red_m[wid] = m2; }
+    const uint32_t m2 = wave_reduce_u32(M2, HP_F16_NEG_INF2, [](uint32_t x, uint32_t y) { return pk_max_f16(x, y); });
+    if (lane == 0) red_m[wid] = m2;
   }
   __syncthreads();                                     // histogram, cell map and wave results complete
 
@@ -918,12 +942,12 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   if (lane == WAVE - 1) { scan_tmp[0][wid] = incl_p; scan_tmp[1][wid] = incl_n; }
   __syncthreads();
 
-  uint32_t mx = 0u, m2 = HP_F16_NEG_INF2;
+  uint32_t m2 = HP_F16_NEG_INF2;
 #pragma unroll
-  for (int w = 0; w < NW; ++w) { mx = pk_max_u16(mx, red_u[w]); m2 = pk_max_f16(m2, red_m[w]); }
-  const uint32_t mag_hi = max(mx & 0xffffu, mx >> 16);
+  for (int w = 0; w < NW; ++w) m2 = pk_max_f16(m2, red_m[w]);
+  const uint32_t mag_hi = sh_out.mag_max;               // 0 unless a logit above the window (or a NaN) was met
   const float m = fmaxf(bf16_lo(m2), bf16_hi(m2));      // exact whenever the row stays on this path
-  const int n_tiny = sh_ntiny, n_ninf = sh_nninf;
+  const int n_tiny = sh_out.n_tiny, n_ninf = sh_out.n_masked;
   int before_p = 0, before_n = 0, tot_p = 0, tot_n = 0; // counts in lower lanes / in the whole segment
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
@@ -942,8 +966,8 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     tz += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(ts);
     if (lane == 0) {
       if (n_tiny) {                                     // e^x = 1 + x, x e^x = x for |x| < 2^-25
-        const double zt = (double)n_tiny + sh_stiny;
-        tz += zt; ts += sh_stiny - (double)m * zt;
+        const double zt = (double)n_tiny + sh_out.s_tiny;
+        tz += zt; ts += sh_out.s_tiny - (double)m * zt;
       }
       sum_d[0] = tz; sum_d[1] = ts;
     }
@@ -1084,7 +1108,7 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
   __shared__ RowResult rr;
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
-  else hist_segment<NT, TOPM>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
+  else hist_segment<NT, TOPM, WPS>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
   finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);
 }

@@ -811,9 +811,12 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   uint32_t vo_after;
   uint32_t M2 = HP_F16_NEG_INF2;                       // packed running maximum of the bf16 patterns (compared as fp16 patterns)
   {
-    // four chunks per lane in flight: a workgroup that streams while its neighbours on the CU are
-    // in their epilogues still covers the HBM latency.  Unrolled by four so that each buffer is
-    // refilled right after it has been counted, without register copies.
+    // DEPTH chunks per lane in flight: a workgroup that streams while its neighbours on the CU are
+    // in their epilogues still covers the HBM latency.  Unrolled by DEPTH so that each buffer is
+    // refilled right after it has been counted, without register copies.  Eight in the build with
+    // 80 registers, which has room for them (measured: no faster than four, also for a workgroup
+    // that is alone on its CU: the CU's counting rate bounds it, not the latency of its loads).
+    constexpr int DEPTH = WPS == 6 ? 8 : 4;
     const int c1 = sg.tail_chunk >= 0 ? sg.c1 - 1 : sg.c1;   // whole chunks; a partial last chunk is counted below
     // The whole chunks are read through a buffer descriptor over exactly their bytes: a lane whose
     // chunk lies past the last whole one gets zeros from the bounds check instead of needing a
@@ -828,39 +831,46 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     uint32_t so = 0u;
 #define C2T_LOAD(k) load_stream_buffer(rs, vo, so + (uint32_t)(k) * (NT * 16u))
 #define C2T_COUNT(q) hist_chunk(q, M2, hist, &sh_out)
-    uint4 qa = C2T_LOAD(0), qb = C2T_LOAD(1), qc = C2T_LOAD(2), qd = C2T_LOAD(3);
+    uint4 q[DEPTH];
+#pragma unroll
+    for (int k = 0; k < DEPTH; ++k) q[k] = C2T_LOAD(k);
     uint16_t* mp = map + tid;
     // Streaming waves issue ahead of the waves of co-resident workgroups that are in their
     // (latency-bound) epilogue or tail: the memory pipeline stays fed.  Measured: 3 % per full layer.
     __builtin_amdgcn_s_setprio(3);
-    // groups of four sweeps in which every lane has a chunk
-    const int n_groups = whole / (4 * NT);
-    for (int it = n_groups; it > 0; --it, so += 4u * NT * 16u, mp += NT) {
-      uint32_t key = C2T_COUNT(qa);
-      qa = C2T_LOAD(4);
-      key = pk_max_f16_raw(key, C2T_COUNT(qb));
-      qb = C2T_LOAD(5);
-      key = pk_max_f16_raw(key, C2T_COUNT(qc));
-      qc = C2T_LOAD(6);
-      key = pk_max_f16_raw(key, C2T_COUNT(qd));
-      qd = C2T_LOAD(7);
-      *mp = (uint16_t)pk_max_f16_raw(key, key >> 16);
+    // groups of DEPTH sweeps in which every lane has a chunk; a cell is four sweeps
+    const int n_groups = whole / (DEPTH * NT);
+    for (int it = n_groups; it > 0; --it, so += (uint32_t)DEPTH * NT * 16u, mp += (DEPTH / 4) * NT) {
+#pragma unroll
+      for (int c = 0; c < DEPTH / 4; ++c) {
+        uint32_t key = C2T_COUNT(q[4 * c]);
+        q[4 * c] = C2T_LOAD(DEPTH + 4 * c);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+          key = pk_max_f16_raw(key, C2T_COUNT(q[4 * c + k]));
+          q[4 * c + k] = C2T_LOAD(DEPTH + 4 * c + k);
+        }
+        mp[c * NT] = (uint16_t)pk_max_f16_raw(key, key >> 16);
+      }
     }
     vo_after = vo;
-    const int g = sg.c0 + (int)(vo >> 4) + n_groups * (4 * NT);
+    const int g0 = sg.c0 + (int)(vo >> 4) + n_groups * (DEPTH * NT);
     __builtin_amdgcn_s_setprio(0);
-    // the last, partial group: up to four chunks of this lane, the row's partial last chunk among them
+    // the last, partial group: up to DEPTH chunks of this lane, the row's partial last chunk among them
     const int tail = sg.tail_chunk;
-    if (g < c1 || g == tail) {
-      uint32_t key = g < c1 ? C2T_COUNT(qa) : hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out);
-      if (g + NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qb));
-      else if (g + NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
-      if (g + 2 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qc));
-      else if (g + 2 * NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
-      if (g + 3 * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(qd));
-      else if (g + 3 * NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
-      *mp = (uint16_t)pk_max_f16(key, key >> 16);
-      M2 = pk_max_f16(M2, key);                       // the partial chunk's maximum is in no other running value
+#pragma unroll
+    for (int c = 0; c < DEPTH / 4; ++c) {
+      const int g = g0 + 4 * c * NT;
+      if (g < c1 || g == tail) {
+        uint32_t key = g < c1 ? C2T_COUNT(q[4 * c]) : hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+          if (g + k * NT < c1) key = pk_max_f16_raw(key, C2T_COUNT(q[4 * c + k]));
+          else if (g + k * NT == tail) key = pk_max_f16(key, hist_chunk_outside(rowp[tail], sg.tail_valid, hist, &sh_out));
+        }
+        mp[c * NT] = (uint16_t)pk_max_f16(key, key >> 16);
+        M2 = pk_max_f16(M2, key);                         // the partial chunk's maximum is in no other running value
+      }
     }
 #undef C2T_COUNT
 #undef C2T_LOAD

@@ -900,9 +900,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   double Z = 0.0, S = 0.0, Zp = 0.0, Sp = 0.0;
   int lane_pos = 0, lane_neg = 0;
   float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
-  uint32_t cw[WPL];                                     // low half: count of +|v_j|, high half: count of -|v_j|
+  const uint32_t w0 = ((uint32_t)(WPL * tid) + HP_WORD_ROT) & (HP_WORDS - 1);   // the lane's words; WPL-aligned: no wrap inside
   {
-    const uint32_t w0 = ((uint32_t)(WPL * tid) + HP_WORD_ROT) & (HP_WORDS - 1);   // WPL-aligned: no wrap inside
+    // low half: count of +|v_j|, high half: count of -|v_j|.  Not kept beyond the sums: the one or
+    // two lanes that need their counts again below read them from LDS again.
+    uint32_t cw[WPL];
 #pragma unroll
     for (int j = 0; j < WPL; j += 4) {
       const uint4 t = *(const uint4*)(hist + w0 + j);
@@ -919,6 +921,9 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     for (int j = 0; j < WPL; ++j)                       // highest of the positive values last
       if (cw[j] & 0xffffu) vtop = hp_value_of_mag(WPL * tid + j, false);
     const double vt = (double)vtop;
+#pragma unroll
+    for (int j = 0; j < WPL; ++j)                       // 64-register build: the halves are unpacked again below rather than
+      if (WPS == 8) asm volatile("" : "+v"(cw[j]));     // kept from above in sixteen registers (which spilled the thread index)
     const bool b3 = ((WPL * tid) & 8) != 0;
     const double e0p = b3 ? ef.ap * ef.cp[3] : ef.ap, e0n = b3 ? ef.an * ef.cn[3] : ef.an;
 #pragma unroll
@@ -991,7 +996,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       int run = above_p;
 #pragma unroll
       for (int j = WPL - 1; j >= 0; --j) {
-        const int n = (int)(cw[j] & 0xffffu);
+        const int n = (int)(hist[w0 + j] & 0xffffu);
         if (run < K && run + n >= K) { sh_tau_rank = HP_WORDS + WPL * tid + j; sh_n_gt = run; }
         run += n;
       }
@@ -1001,7 +1006,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       int run = above_n;
 #pragma unroll
       for (int j = 0; j < WPL; ++j) {
-        const int n = (int)(cw[j] >> 16);
+        const int n = (int)(hist[w0 + j] >> 16);
         if (run < K && run + n >= K) { sh_tau_rank = HP_WORDS - 1 - (WPL * tid + j); sh_n_gt = run; }
         run += n;
       }
@@ -1038,7 +1043,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     if (part_p || part_n) {
       LaneCounts<WPL> counts;
 #pragma unroll
-      for (int j = 0; j < WPL; ++j) counts.w[j] = cw[j];
+      for (int j = 0; j < WPL; ++j) counts.w[j] = hist[w0 + j];
       const TopMPart part = top_m_boundary_lane<WPL>(tid, counts, part_p, part_p ? above_p : above_n, M, vt);
       zm += part.zm; sm += part.sm;
     }

@@ -164,12 +164,13 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
     sp.lds_bytes = (int)lds;
     const int topm = c.entropy_top_m > 0;
-    // Two builds of the kernel.  Four workgroups per CU on 64 registers a lane (a few spills in the
-    // epilogue) when that lets the launch run in one round that three per CU could not hold;
-    // otherwise three per CU on 80 registers, which is faster per workgroup (measured: launches of
-    // many rounds 9 % faster, launches that do not fill the chip 5 % faster).
+    // Two builds of the kernel.  Four workgroups per CU on 64 registers a lane, or three per CU on
+    // 80 registers.  Measured on full layers of V = 128256 (us per layer, four / three per CU):
+    // 256 rows 32.4 / 31.6, 512: 38.8 / 39.8, 1024: 61.0 / 73.1, 1280: 82.7 / 86.6, 1536: 95.3 / 91.6,
+    // 2048: 114 / 120, 3072: 166 / 163, 4096: 209 / 215, 8192: 388 / 393.  Four per CU whenever a CU
+    // gets more than one workgroup; a workgroup that is alone on its CU is 2-3 % faster on 80 registers.
     const int64_t cus = x->n_cus;
-    const bool four_per_cu = (int64_t)grid > 3 * cus && (int64_t)grid <= 4 * cus;
+    const bool four_per_cu = (int64_t)grid > cus;
     const void* fn = topm ? (four_per_cu ? (const void*)k_logits_hist<HP_NT, true, 8> : (const void*)k_logits_hist<HP_NT, true, 6>)
                           : (four_per_cu ? (const void*)k_logits_hist<HP_NT, false, 8> : (const void*)k_logits_hist<HP_NT, false, 6>);
     size_t& raised = x->lds_raised[four_per_cu ? 1 : 0];

@@ -159,6 +159,10 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   ScoreParams sp;
   sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
   sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.B = c.batch; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
+  // one round of workgroups (static placement), more of them than CUs, and few enough sequences:
+  // deal the live rows round the CUs
+  sp.compact = (rows_per_seq > 1 && (int64_t)grid > (int64_t)x->n_cus && (int64_t)grid <= 4 * (int64_t)x->n_cus &&
+                c.batch <= COMPACT_MAX_B) ? 1 : 0;
   sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m; sp.D = c.max_depth;
   if (c.logits_dtype == C2T_BF16) {
     const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);

@@ -500,20 +500,63 @@ __device__ __forceinline__ void end_of_sequence(const TreeState& st, const Score
 }
 
 // Which frontier slot of which sequence a workgroup (index w among the launched rows) takes.
-// Workgroups are placed in index order, four to a CU.  A layer whose frontiers are (nearly) full
-// runs fastest in slot-major order (consecutive workgroups = the same slot of consecutive
-// sequences: full layers 2 % faster at B = 64 and B = 256 than sequence-major).  In a thinned-out
-// layer only the low slots of every sequence are live, and slot-major order would put all live rows
-// first, i.e. four to a CU on a quarter of the chip; sequence-major order interleaves them with
-// workgroups that exit at once, which spreads them (290 live rows of 1024: 44 against 54 us).
-// The number of live rows of the layer is known on the device (the previous layer counted it).
+// A launch that fits the chip in one round (at most four workgroups per CU) is placed statically:
+// workgroup w runs on CU w mod n_cus (HW_ID read-outs), so a CU hosts w, w + n_cus, w + 2 n_cus, ...
+// Full layers run fastest in slot-major order (consecutive workgroups = the same slot of
+// consecutive sequences: 2 % faster at B = 64 and B = 256 than sequence-major).  In a thinned-out
+// layer the frontiers are of very different lengths (many sequences have used their budget up,
+// others are still full), and a fixed order leaves some CUs with four live rows and others with
+// none: the layer then takes as long as a full one.  With `compact` the workgroup takes the w-th
+// LIVE row in slot-major order instead, which it finds from the frontier sizes alone (every wave
+// by itself: one load per lane and at most launched/64 ballots, no atomics, no barrier): the live
+// rows are dealt round the CUs, at most one more on one CU than on another.  Workgroups past the
+// live rows take the sequences without a frontier (one each, for the loop guard) or exit.
 struct RowOfWorkgroup { int b, f, nf; };
+// position of the n-th set bit of m (n < popcount(m)); uniform over the wave
+__device__ __forceinline__ int nth_set_bit(uint64_t m, int n) {
+  const int lane = lane_id();
+  const int below = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+  const uint64_t hit = __builtin_amdgcn_ballot_w64(((m >> lane) & 1ull) != 0ull && below == n);
+  return (int)__builtin_ctzll(hit);
+}
+constexpr int COMPACT_MAX_B = 256;            // frontier sizes held by one wave: four per lane
 __device__ __forceinline__ RowOfWorkgroup row_of_workgroup(const TreeState& st, const ScoreParams& sp, int w) {
   const int* nfs = st.nf[sp.layer & 1];
+  RowOfWorkgroup r;
+  if (sp.compact) {
+    const int lane = lane_id();
+    int nfv[COMPACT_MAX_B / WAVE];
+#pragma unroll
+    for (int k = 0; k < COMPACT_MAX_B / WAVE; ++k) { const int i = lane + k * WAVE; nfv[k] = i < sp.B ? nfs[i] : -1; }
+    int run = 0, b = -1, f = 0, nf = 0;
+    for (int ff = 0; ff < sp.rows_per_seq && b < 0; ++ff) {
+#pragma unroll
+      for (int k = 0; k < COMPACT_MAX_B / WAVE; ++k) {
+        if (k * WAVE >= sp.B) break;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(nfv[k] > ff);
+        const int c = __builtin_popcountll(m);
+        if (b < 0 && w < run + c) { b = k * WAVE + nth_set_bit(m, w - run); f = ff; nf = ff + 1; }   // any nf > f does
+        run += c;
+      }
+    }
+    if (b < 0) {                                          // run = all live rows of the layer
+      int d = w - run;
+#pragma unroll
+      for (int k = 0; k < COMPACT_MAX_B / WAVE; ++k) {
+        if (k * WAVE >= sp.B) break;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(nfv[k] == 0);
+        const int c = __builtin_popcountll(m);
+        if (b < 0 && d >= 0 && d < c) { b = k * WAVE + nth_set_bit(m, d); f = 0; nf = 0; }
+        d -= c;
+      }
+    }
+    if (b < 0) { b = 0; f = 1; nf = 1; }                 // nothing left for this workgroup
+    r.b = __builtin_amdgcn_readfirstlane(b); r.f = __builtin_amdgcn_readfirstlane(f); r.nf = __builtin_amdgcn_readfirstlane(nf);
+    return r;
+  }
   const int b_seq = w / sp.rows_per_seq, b_slot = w % sp.B;
   const int nf_seq = nfs[b_seq], nf_slot = nfs[b_slot];         // both loads issued before the choice: no dependent round trip
   const bool slot_major = 4 * st.layer_rows[sp.layer] >= 3 * sp.B * sp.rows_per_seq;
-  RowOfWorkgroup r;
   r.b = slot_major ? b_slot : b_seq;
   r.f = slot_major ? w / sp.B : w % sp.rows_per_seq;
   r.nf = slot_major ? nf_slot : nf_seq;

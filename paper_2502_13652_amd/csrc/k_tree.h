@@ -81,6 +81,7 @@ struct ScoreParams {
   int nsplit, rows_per_seq, B, F, K, N, h, layer, D;
   int M;                                                     // 0: entropy over the whole row; M > 0: over the M largest logits
   int lds_bytes;                                             // dynamic LDS of the launch
+  int compact;                                               // 1: workgroup w takes the w-th live row (see row_of_workgroup)
   float z_beta;
 };
 

@@ -244,6 +244,12 @@ LIMIT_CASES = {
     "wide_frontier_keep_all": (2, 9000, "bf16", 3, 64, 16, 8, 0.0, 1024),
     "tiny_vocab": (5, 70, "bf16", 4, 8, 8, 4, 0.1, 30),
     "budget_one": (4, 1000, "f32", 3, 4, 4, 4, 0.0, 1),
+    # launches of one round with more workgroups than CUs deal the live rows round the CUs: batch sizes
+    # that are not multiples of the wave size, small budgets (frontiers of very different lengths,
+    # sequences without a frontier in the later layers), both kernels, the largest such batch
+    "dealt_rows_b100": (100, 3001, "bf16", 5, 8, 8, 8, 0.3, 12),
+    "dealt_rows_b200_f32": (200, 1003, "f32", 4, 4, 4, 4, 0.3, 6),
+    "dealt_rows_b256": (256, 517, "bf16", 4, 4, 4, 4, 0.4, 5),
 }
 
 

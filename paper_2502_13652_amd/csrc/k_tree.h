@@ -217,9 +217,12 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
 // the order-preserving key of z finds the bin that holds the n_keep-th largest z, and the list is
 // cut down to the survivors from that bin upwards before the exact ranking.  The ranking gives each
 // survivor to T = 2^tshift lanes, which split the list between them and read 32 values per step
-// (the LDS is busy with the neighbouring workgroups' histograms: dependent reads are slow).
+// (the LDS is busy with the neighbouring workgroups' histograms: dependent reads are slow); a list
+// of at most 64 survivors (root layers, chains, narrow trees) leaves a lane at most eight values,
+// which it reads one at a time instead (measured: 1-2 us per layer of a single sequence).
 constexpr int PRUNE_HIST_WORDS = 2048;        // 4096 bins, two 16-bit counters per word
 constexpr int PRUNE_PRESELECT_MIN = 128;      // shorter lists are ranked directly
+constexpr int PRUNE_SHORT_LIST = 64;          // up to here the lanes of a survivor read the list one value at a time
 
 __host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
   (void)h;
@@ -349,7 +352,16 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
         if (s.h_tok) par_s = s.fr_s[(int64_t)b * F + i / K];
       }
       int rank = 0;
-      if (mine) {
+      if (mine && ns <= PRUNE_SHORT_LIST) {                  // short list: one value per lane and step, at most eight steps
+        for (int v = sub; v < ns; v += T) {
+          const float q = sz[v];
+          if (q > z) rank += 1;
+          else if (q == z && v != u) {                       // ties in z: rare
+            const int tj = stok[v], ij = sidx[v];
+            rank += (tj < tok) || (tj == tok && ij < i);
+          }
+        }
+      } else if (mine) {
         for (int v = sub * 32; v < ns; v += T * 32) {        // entries past ns are masked
           float qa[32];
 #pragma unroll

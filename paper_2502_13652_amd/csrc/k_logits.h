@@ -535,7 +535,10 @@ __device__ __forceinline__ RowOfWorkgroup row_of_workgroup(const TreeState& st, 
         if (k * WAVE >= sp.B) break;
         const uint64_t m = __builtin_amdgcn_ballot_w64(nfv[k] > ff);
         const int c = __builtin_popcountll(m);
-        if (b < 0 && w < run + c) { b = k * WAVE + nth_set_bit(m, w - run); f = ff; nf = ff + 1; }   // any nf > f does
+        if (b < 0 && w < run + c) {
+          const int bl = nth_set_bit(m, w - run);
+          b = k * WAVE + bl; f = ff; nf = __builtin_amdgcn_readlane(nfv[k], bl);
+        }
         run += c;
       }
     }
@@ -584,7 +587,7 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else generic_segment<DT, NT, 1>(rowp, V, K, sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
-  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1168,7 +1171,7 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else hist_segment<NT, TOPM, WPS>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
-  finish_layer<NT>(st, sp, b, f, split, rl, rr, dyn_lds, cls);
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls);
 }
 
 // Plain streaming read: the practical HBM ceiling.

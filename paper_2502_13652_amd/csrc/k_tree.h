@@ -230,7 +230,7 @@ __host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
 }
 
 template <int NT>
-__device__ __forceinline__ void prune_sequence(const TreeState& s, const ScoreParams& sp, int b, unsigned char* lds) {
+__device__ __forceinline__ void prune_sequence(const TreeState& s, const ScoreParams& sp, int b, int nf, unsigned char* lds) {
   constexpr int NW = NT / WAVE;
   const int F = sp.F, K = sp.K, N = sp.N, layer = sp.layer;
   const float z_beta = sp.z_beta;
@@ -259,7 +259,6 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     }
   }
   const uint32_t info = tid < F ? ld_dev(s.row_info + (int64_t)b * F + tid) : 0u;
-  const int nf = s.nf[layer & 1][b];
   const int nn = s.n_nodes[b];
   // the kept flags start at zero (all F*K slots: slots of unused rows are unspecified anyway); stored
   // now, so that they are long complete when the ranking stores the ones
@@ -424,8 +423,11 @@ __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
   if (threadIdx.x < WAVE) {
     wait_vector_memory();
     if (threadIdx.x == 0) {
-      sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
-      if (sh_last) st_dev(ticket, 0);
+      if (expected == 1) sh_last = 1;                      // the only arrival (root layers, chains): no round trip to the counter
+      else {
+        sh_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
+        if (sh_last) st_dev(ticket, 0);
+      }
     }
   }
   __syncthreads();
@@ -437,7 +439,7 @@ __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
 // workgroup that completes a sequence's last row prunes and appends.  Both overlap with the other
 // workgroups' streaming, so the whole layer is one launch.
 template <int NT>
-__device__ __forceinline__ void finish_layer(const TreeState& s, const ScoreParams& sp, int b, int f, int split,
+__device__ __forceinline__ void finish_layer(const TreeState& s, const ScoreParams& sp, int b, int f, int nf, int split,
                                              int64_t row_launched, RowResult& rr, unsigned char* lds,
                                              const float* __restrict__ cls) {
   const int tid = threadIdx.x, K = sp.K;
@@ -450,8 +452,8 @@ __device__ __forceinline__ void finish_layer(const TreeState& s, const ScorePara
     merge_row(sp, row_launched, rr, lds, (size_t)sp.lds_bytes);
   }
   score_row(s, sp, b, f, rr, cls);
-  if (!last_arrival(s.tickets + b, s.nf[sp.layer & 1][b])) return;
-  prune_sequence<NT>(s, sp, b, lds);
+  if (!last_arrival(s.tickets + b, nf)) return;              // nf: the sequence's frontier size, known since the workgroup started
+  prune_sequence<NT>(s, sp, b, nf, lds);
 }
 
 struct TreeOut {

@@ -165,8 +165,10 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
                 c.batch <= COMPACT_MAX_B) ? 1 : 0;
   sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m; sp.D = c.max_depth;
   if (c.logits_dtype == C2T_BF16) {
-    const size_t lds = std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds);
-    sp.lds_bytes = (int)lds;
+    const size_t lds_work = (std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds) + 15) / 16 * 16;
+    sp.lds_bytes = (int)lds_work;
+    sp.w_lds_off = (int)lds_work;                           // behind it: the classifier's parameters, padded to 16 bytes
+    const size_t lds = lds_work + ((size_t)(5 * c.hidden + 1) * 4 + 15) / 16 * 16;
     const int topm = c.entropy_top_m > 0;
     // Two builds of the kernel.  Four workgroups per CU on 64 registers a lane, or three per CU on
     // 80 registers.  Measured on full layers of V = 128256 (us per layer, four / three per CU):
@@ -192,6 +194,7 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
     sp.lds_bytes = (int)lds;
+    sp.w_lds_off = -1;
     hipExtLaunchKernelGGL((k_logits_generic<0, NT_F32>), dim3(grid), dim3(NT_F32), lds, s, ev0, ev1, 0, logits, stride,
                           c.vocab, cps, (const float*)x->st.cls, x->st, sp);
   }

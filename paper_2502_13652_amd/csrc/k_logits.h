@@ -587,7 +587,7 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else generic_segment<DT, NT, 1>(rowp, V, K, sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
-  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls);    // split records are indexed by launched row
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, nullptr);    // split records are indexed by launched row
 }
 
 // ---------------------------------------------------------------------------------------
@@ -825,6 +825,20 @@ __device__ __noinline__ TopMPart top_m_boundary_lane(int tid, LaneCounts<WPL> co
   return r;
 }
 
+// A thread's share of the classifier's parameters on its way from global memory to LDS.
+struct ClassifierStage { float4 q; float* dst; bool mine; };
+__device__ __forceinline__ ClassifierStage stage_classifier(const float* __restrict__ cls, int h, float* dst) {
+  ClassifierStage c;
+  c.dst = dst;
+  c.mine = dst != nullptr && (int)threadIdx.x * 4 < 5 * h + 1;     // the array is padded to a multiple of four floats
+  c.q = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (c.mine) c.q = ((const float4*)cls)[threadIdx.x];
+  return c;
+}
+__device__ __forceinline__ void store_classifier(const ClassifierStage& c) {
+  if (c.mine) ((float4*)c.dst)[threadIdx.x] = c.q;
+}
+
 // One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
 // TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
@@ -832,7 +846,8 @@ __device__ __noinline__ TopMPart top_m_boundary_lane(int tid, LaneCounts<WPL> co
 template <int NT, bool TOPM, int WPS>
 __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
-                                             unsigned char* map_lds, const SelectLds& sel, RowResult* rr) {
+                                             unsigned char* map_lds, const SelectLds& sel, RowResult* rr,
+                                             const ClassifierStage cst) {
   constexpr int NW = NT / WAVE;
   constexpr int WPL = HP_WORDS / NT;                   // words per lane in the epilogue (8 at 512 threads)
   static_assert(NW <= 16 && WPL % 4 == 0, "one DPP row holds the per-wave partials; a lane reads whole 16-byte runs");
@@ -900,6 +915,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       }
     }
     vo_after = vo;
+    store_classifier(cst);                               // published by the barriers below
     const int g0 = sg.c0 + (int)(vo >> 4) + n_groups * (DEPTH * NT);
     __builtin_amdgcn_s_setprio(0);
     // the last, partial group: up to DEPTH chunks of this lane, the row's partial last chunk among them
@@ -1168,10 +1184,16 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
   const Segment sg = make_segment<8>(V, split, cps);
   __shared__ RowResult rr;
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
-  if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
+  // The classifier's parameters (5h+1 <= 1281 floats) are copied to LDS for the scoring step: the
+  // loads are issued now, four floats a thread, and stored behind the streaming loop.
+  const ClassifierStage cst = stage_classifier(cls, sp.h, (!TOPM && sp.w_lds_off >= 0) ? (float*)(dyn_lds + sp.w_lds_off) : nullptr);
+  if (sg.ncell == 0) {                                     // (loaded again here: the copy above must not stay in registers for this)
+    store_classifier(stage_classifier(cls, sp.h, cst.dst));
+    if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; }
+  }
   else hist_segment<NT, TOPM, WPS>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
-                        make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr);
-  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls);
+                        make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr, cst);
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, cst.dst);
 }
 
 // Plain streaming read: the practical HBM ceiling.

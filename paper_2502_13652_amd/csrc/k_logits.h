@@ -226,6 +226,29 @@ __device__ __forceinline__ int rank_list(int K, const SelectLds& sel, const int3
   const float* el_v = (const float*)sel.list;
   const int32_t* el_i = (const int32_t*)(sel.list + (size_t)sel.list_cap * 4);
   const int n_el = min(*sh_cnt, sel.list_cap);
+  if (n_el <= 64) {
+    // short list (the usual case: K to 2K-1 elements): T lanes per element, each compares it with
+    // every T-th entry, one value per step; the partial ranks are summed over the T lanes
+    int tshift = 0;
+    while (tshift < 4 && (n_el << (tshift + 1)) <= NT) ++tshift;
+    const int T = 1 << tshift, e = tid >> tshift, sub = tid & (T - 1);
+    const bool mine = e < n_el;
+    const float v = mine ? el_v[e] : 0.f; const int id = mine ? el_i[e] : 0;
+    int rank = 0;
+    if (mine) {
+      for (int o = sub; o < n_el; o += T) {
+        const float q = el_v[o];
+        if (q > v) rank += 1;
+        else if (q == v && o != e) rank += el_i[o] < id;
+      }
+    }
+    if (tshift >= 1) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 2) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR2, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 3) rank += (int)dpp_u32<C2T_DPP_ROW_HALF_MIRROR, 0xf>(0u, (uint32_t)rank);
+    if (tshift >= 4) rank += (int)dpp_u32<C2T_DPP_ROW_MIRROR, 0xf>(0u, (uint32_t)rank);
+    if (mine && sub == 0 && rank < K) { topv[rank] = v; topi[rank] = id; }
+    return min(n_el, K);
+  }
 #pragma unroll 1
   for (int e = tid; e < n_el; e += NT) {
     const float v = el_v[e]; const int id = el_i[e];

@@ -1104,10 +1104,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   // could be among the top K, which the histogram cannot rank), or if fewer than K logits lie
   // in the window while some are masked (the top K then ends with masked entries).
   const int n_elems = (sg.tail_chunk >= 0 ? (sg.ncell - 1) * 8 + sg.tail_valid : sg.ncell * 8);
-  // With the entropy over the M largest logits: also if logits below the window could be among them.
+  // With the entropy over the M largest logits: also if some but not all of the logits below the
+  // window are among them (which ones cannot be told from the histogram).
   if (mag_hi >= HP_MAG_LO + HP_MAG_SPAN || tot_p + tot_n + n_tiny + n_ninf != n_elems || (n_tiny > 0 && sh_tau_rank < HP_WORDS) ||
       (n_ninf > 0 && sh_tau_rank < 0) ||
-      (TOPM && n_tiny > 0 && tot_p < M)) {
+      (TOPM && n_tiny > 0 && tot_p < M && M < tot_p + n_tiny)) {
     __syncthreads();
     generic_segment<1, NT, HP_CPC>(rowp, V, K, M, sg, map_lds, sel, rr, 2u);
     return;
@@ -1117,7 +1118,8 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     // top: its positive magnitudes descending, then its negative ones ascending; `above` of them
     // lie in other lanes.  Same reference chain as for S (lane top, wave top, m): one sign throughout.
     double zm = 0.0, sm = 0.0;
-    const int above_p = tot_p - (before_p + incl_p), above_n = tot_p + before_n + incl_n - lane_neg;
+    // (logits below the window, |x| < 2^-25, rank between the positive and the negative window values)
+    const int above_p = tot_p - (before_p + incl_p), above_n = tot_p + n_tiny + before_n + incl_n - lane_neg;
     const double vt = (double)vtop;
     // A lane whose positive (negative) values all rank within the first M contributes the sums it
     // already has; only the lane that holds the M-th largest logit walks its bins.
@@ -1143,7 +1145,13 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       tz += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(tz); ts += dpp_f64<C2T_DPP_QUAD_XOR2, 0xf>(ts);
       tz += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_HALF_MIRROR, 0xf>(ts);
       tz += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(tz); ts += dpp_f64<C2T_DPP_ROW_MIRROR, 0xf>(ts);
-      if (lane == 0) { sum_m[0] = tz; sum_m[1] = ts; }
+      if (lane == 0) {
+        if (n_tiny > 0 && tot_p < M) {                    // then M >= tot_p + n_tiny: all of them are among the M largest
+          const double zt = (double)n_tiny + sh_out.s_tiny;
+          tz += zt; ts += sh_out.s_tiny - (double)m * zt;
+        }
+        sum_m[0] = tz; sum_m[1] = ts;
+      }
     }
   }
   float tau = -INFINITY;

@@ -57,6 +57,11 @@ def adversarial_rows(V, rng, bf16):
     add("zeros_with_positive_head", zh)                                  # below-window values inside the fast path
     tn = 3 * rng.standard_normal(V); tn[rng.random(V) < 0.01] = 1e-9; tn[rng.random(V) < 0.01] = -1e-12
     add("sprinkled_tiny", tn)
+    # few positive logits, a few below-window ones, the rest negative: the M largest (M = 1000) then
+    # take all positives, all below-window values and only some of the negative ones
+    fp = -5 + rng.standard_normal(V); fp[rng.choice(V, min(V, 200), replace=False)] = rng.uniform(1, 5, min(V, 200))
+    fp[rng.choice(V, min(V, 30), replace=False)] = rng.choice([0.0, -0.0, 1e-9, -1e-12], min(V, 30))
+    add("few_positive_some_tiny", fp)
     lowhigh = -20 + rng.standard_normal(V); lowhigh[V // 2:] += 60       # reference must be raised mid-row
     add("late_large", lowhigh)
     if V > 70000:

@@ -551,7 +551,7 @@ __global__ __launch_bounds__(RR_NT) void k_finalize_rerank(TreeState s, TreeOut 
   int32_t* pos = s.h_pos + (int64_t)b * total;
   __shared__ uint32_t dig[4096];
   __shared__ int32_t scan_w[NW];
-  __shared__ int32_t sh_digit, sh_above, sh_total, sh_n;
+  __shared__ int32_t sh_digit, sh_above, sh_n;
   __shared__ float sel_s[C2T_MAX_BUDGET_DEV];
   __shared__ int32_t sel_i[C2T_MAX_BUDGET_DEV], sel_par[C2T_MAX_BUDGET_DEV], sel_depth[C2T_MAX_BUDGET_DEV];
   // a thread owns a contiguous range of history indices, so that index order = thread order

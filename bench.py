@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--no-full-layer", action="store_true",
                     help="skip the extra full-layer launches (roofline.full_layer), so that a kernel trace of the run "
                          "holds the warm-up and timed draft phases only")
+    ap.add_argument("--profile-every", type=int, default=4, help="steps of the timed region between two steps whose launches carry timing events")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -108,7 +109,11 @@ def main():
             step()
         torch.cuda.synchronize()
     else:
+        # the per-dispatch events cost the host about 20 us a launch, which shows in the step time: they
+        # are attached to every --profile-every-th step of the timed region only
         ctx.profile_enable(a.steps * D)
+        every = a.profile_every if a.steps >= a.profile_every else 1
+        ctx.profile_sample(every, every // 2)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(a.steps):
@@ -119,10 +124,11 @@ def main():
     ctx.profile_enable(0)
     rows = ctx.layer_rows().cpu().numpy()[:D].astype(np.int64)      # rows consumed by each layer's expand
     scored_per_step = int(rows.sum()) * K
-    k1_ms = np.array(k1_ms, np.float64).reshape(a.steps, D)
+    n_sampled = len(k1_ms) // D                                     # steps whose launches carried events
+    k1_ms = np.array(k1_ms[:n_sampled * D], np.float64).reshape(n_sampled, D)
     bytes_layer = rows * V * esz
     k1_total_s = k1_ms.sum() / 1e3
-    achieved = bytes_layer.sum() * a.steps / k1_total_s / 1e9       # GB/s over every logits-pass launch
+    achieved = bytes_layer.sum() * n_sampled / k1_total_s / 1e9       # GB/s over every logits-pass launch
     per_layer = [dict(layer=int(l), rows=int(rows[l]), mbytes=round(bytes_layer[l] / 1e6, 2),
                       us=round(float(k1_ms[:, l].mean() * 1e3), 2),
                       gbps=round(float(bytes_layer[l] / (k1_ms[:, l].mean() / 1e3) / 1e9), 1)) for l in range(D)]
@@ -203,11 +209,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, cfg["desc"]), "B": B, "V": V, "logits": cfg["dtype"], "D": D,
-                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "mask_frac": a.mask_frac, "hip_graph": bool(a.graph), "classifier_seed": W.classifier_seed(a.workload),
+                   "F": F, "K": K, "h": h, "beta": cfg["beta"], "N": N, "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "mask_frac": a.mask_frac, "hip_graph": bool(a.graph), "profile_every": a.profile_every, "classifier_seed": W.classifier_seed(a.workload),
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "k_logits_hist<512>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>", "launches": int(a.steps * D),
+                     "kernel": "k_logits_hist<512>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>", "launches": int(n_sampled * D), "sampled_steps": int(n_sampled),
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),
                      "full_layer": full_layer,

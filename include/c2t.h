@@ -175,8 +175,13 @@ int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
  * stream (they take the kernel's own begin and end).  c2t_profile_enable creates `capacity` event
  * pairs (host resources; 0 disables and destroys them).  After the caller has synchronised the
  * stream, c2t_profile_read writes the duration in milliseconds of each launch recorded since the
- * last read to ms[0..*n) ([host], capacity given in *n on entry) and forgets them. */
+ * last read to ms[0..*n) ([host], capacity given in *n on entry) and forgets them.
+ * Attaching the events costs the host about 20 us a launch; c2t_profile_sample(every, first)
+ * attaches them only to the launches of draft phases first, first + every, first + 2 every, ...
+ * (phases are counted in c2t_reset calls since c2t_profile_enable, from 0); every >= 1,
+ * 0 <= first < every, else C2T_ERR_INVALID_ARG; default: every phase. */
 int c2t_profile_enable(c2t_ctx* ctx, int32_t capacity);
+int c2t_profile_sample(c2t_ctx* ctx, int32_t every, int32_t first);
 int c2t_profile_read(c2t_ctx* ctx, float* ms, int32_t* n);
 
 /* Plain streaming read of `bytes` (multiple of 16) of [device] memory, summed into one

@@ -79,6 +79,7 @@ def load_library():
     L.c2t_set_row_splits.argtypes = [vp, i32, i32]
     L.c2t_profile_enable.argtypes = [vp, i32]
     L.c2t_profile_read.argtypes = [vp, vp, P(i32)]
+    L.c2t_profile_sample.argtypes = [vp, i32, i32]
     L.c2t_stream_read.argtypes = [vp, sz, vp, vp]
     L.c2t_stream_read_rows.argtypes = [vp, i32, sz, sz, vp, vp]
     L.c2t_strerror.argtypes = [ctypes.c_int]
@@ -212,6 +213,10 @@ class C2TContext:
 
     def profile_enable(self, capacity):
         _check(self.L.c2t_profile_enable(self.ctx, capacity), "c2t_profile_enable")
+
+    def profile_sample(self, every, first=0):
+        """Attach the timing events only to the launches of draft phases first, first + every, ..."""
+        _check(self.L.c2t_profile_sample(self.ctx, every, first), "c2t_profile_sample")
 
     def profile_read(self, capacity):
         buf = (ctypes.c_float * capacity)()

@@ -128,6 +128,7 @@ struct c2t_ctx {
   std::vector<hipEvent_t> ev;
   std::vector<float> cls_host;
   int ev_used;
+  int sample_every, sample_first, phase_no;   // events go to the launches of draft phases sample_first, sample_first + sample_every, ...
 };
 
 namespace {
@@ -249,7 +250,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   x->part_topi = (int32_t*)(w + L.part_topi);
   x->tab_e = (double*)(w + L.tab_e);
   x->z_beta = cfg->beta <= 0.0f ? -INFINITY : (float)std::log((double)cfg->beta / (1.0 - (double)cfg->beta));
-  x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0;
+  x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0; x->sample_every = 1; x->sample_first = 0; x->phase_no = -1;
   x->lds_raised[0] = x->lds_raised[1] = 48 * 1024;
   {
     int dev = 0, n = 0;
@@ -296,7 +297,7 @@ int c2t_reset(c2t_ctx* x, void* stream) {
   hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, x->st, x->cfg.batch,
                      x->cfg.max_frontier, x->cfg.max_depth);
   if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
-  x->layer = 0; x->finalized = false;
+  x->layer = 0; x->finalized = false; x->phase_no += 1;
   return C2T_OK;
 }
 
@@ -311,7 +312,7 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
   const bool first = x->layer == 0;
   const int rows_per_seq = first ? 1 : c.max_frontier;
   const int nsplit = first ? x->ns_first : x->ns_other;
-  const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size();
+  const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size() && x->phase_no % x->sample_every == x->sample_first;
   hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, s,
                                timed ? x->ev[x->ev_used] : nullptr, timed ? x->ev[x->ev_used + 1] : nullptr);
   if (e != hipSuccess) return C2T_ERR_HIP;
@@ -394,12 +395,18 @@ int c2t_set_row_splits(c2t_ctx* x, int32_t first_layer, int32_t other_layers) {
 int c2t_profile_enable(c2t_ctx* x, int32_t capacity) {
   if (!x || capacity < 0) return C2T_ERR_INVALID_ARG;
   for (hipEvent_t e : x->ev) (void)hipEventDestroy(e);
-  x->ev.clear(); x->ev_used = 0;
+  x->ev.clear(); x->ev_used = 0; x->phase_no = -1;           // the next draft phase is phase 0
   for (int i = 0; i < 2 * capacity; ++i) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return C2T_ERR_HIP;
     x->ev.push_back(e);
   }
+  return C2T_OK;
+}
+
+int c2t_profile_sample(c2t_ctx* x, int32_t every, int32_t first) {
+  if (!x || every < 1 || first < 0 || first >= every) return C2T_ERR_INVALID_ARG;
+  x->sample_every = every; x->sample_first = first;
   return C2T_OK;
 }
 

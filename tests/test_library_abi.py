@@ -75,6 +75,8 @@ def test_workspace_and_state_errors(lib):
     p = ctypes.c_void_p()
     assert lib.c2t_get_frontier(ctx, ctypes.byref(p), None, None) == 0 and p.value
     assert lib.c2t_get_layer_rows(ctx, None) == -1
+    assert lib.c2t_profile_sample(ctx, 0, 0) == -1 and lib.c2t_profile_sample(ctx, 4, 4) == -1
+    assert lib.c2t_profile_sample(ctx, 4, 2) == 0 and lib.c2t_profile_sample(None, 1, 0) == -1
     lib.c2t_destroy(ctx)
     lib.c2t_destroy(None)
     assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3)

@@ -90,7 +90,7 @@ def run_both(cfg, cls, layer_logits, seqs=None, splits=None, per_layer=True, tag
         x = layer_logits(l)
         g.expand_layer(x)
         torch.cuda.synchronize()
-        xs = W.as_numpy_bits(x[seqs])
+        xs = W.as_numpy_bits(x if len(seqs) == B and seqs == list(range(B)) else x[seqs])
         if o.frontier()["n_frontier"].sum() > 0:
             o.expand_layer(xs, threads=ORACLE_THREADS)
             if per_layer:

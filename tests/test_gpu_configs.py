@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import workloads as W
-from _harness import run_both, to_np, make_gpu
+from _harness import run_both, to_np, make_gpu, ORACLE_THREADS
 
 pytestmark = pytest.mark.gpu
 
@@ -37,25 +37,19 @@ def test_single_sequence_configs(name, instance):
     print(name, "n_nodes", oo["n_nodes"], "scored", audit["scored"], "margins", audit["min_thr_margin"], audit["min_rank_gap"])
 
 
-@pytest.mark.parametrize("name,sample", [("cfg4", 8), ("cfg5", 6)])
-def test_batched_configs_full_size_sampled_oracle(name, sample):
+@pytest.mark.parametrize("name,instance", [("cfg4", 0), ("cfg4", 1), ("cfg5", 0), ("cfg5", 1)])
+def test_batched_configs_every_sequence_against_oracle(name, instance):
+    # full batch on the GPU, and the oracle replays EVERY sequence (sharded over the host's threads),
+    # layer by layer and at the end
     cfg = W.CONFIGS[name]
     cls = W.classifier(cfg, W.classifier_seed(name))
-    rng = np.random.default_rng(7)
-    seqs = sorted(rng.choice(cfg["B"], sample, replace=False).tolist())
-    print("config", name, "oracle on sequences", seqs, flush=True)
-    go, oo, audit = run_both(cfg, cls, _layers(cfg, name, keep=False), seqs=seqs, tag=name)
+    print("config", name, "instance", instance, "oracle on all", cfg["B"], "sequences", flush=True)
+    go, oo, audit = run_both(cfg, cls, _layers(cfg, name, instance=instance, keep=False), tag="%s inst %d" % (name, instance))
     n = go["n_nodes"]
     assert (n <= cfg["N"]).all() and n.sum() > 0
-    # properties that hold for every sequence of the full batch, not only the sampled ones
-    for b in range(cfg["B"]):
-        k = int(n[b])
-        par = go["parent"][b, :k]
-        assert (par < np.arange(k)).all()
-        m = go["mask"][b]
-        assert (m.sum(axis=1)[:k] == go["position"][b, :k]).all()     # ancestors + self = depth + 1
-        assert not m[k:].any()
-    print(name, "nodes/seq mean %.1f" % n.mean(), "min margins", audit["min_thr_margin"].min(), audit["min_rank_gap"].min())
+    assert int(audit["scored"].sum()) > cfg["B"] * cfg["K"]            # the trees grow beyond the root layer
+    print(name, "instance", instance, "nodes/seq mean %.1f" % n.mean(), "scored", int(audit["scored"].sum()),
+          "min margins", audit["min_thr_margin"].min(), audit["min_rank_gap"].min())
 
 
 @pytest.mark.parametrize("name,sample,frac", [("cfg2", 1, 0.3), ("cfg4", 6, 0.01), ("cfg4", 6, 0.9)])
@@ -82,7 +76,7 @@ def test_masked_vocabulary_whole_trees(name, sample, frac):
         assert not (go["status"] & 2).any()               # no row left the histogram path
 
 
-@pytest.mark.parametrize("name,sample", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 6)])
+@pytest.mark.parametrize("name,sample", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 64), ("cfg5", 256)])
 def test_entropy_over_top_1000_whole_trees(name, sample):
     # the paper's own configuration of the H feature: Eq. 2, second line with M = 1000
     cfg = dict(W.CONFIGS[name], entropy_top_m=1000)
@@ -116,8 +110,8 @@ def _compare_reranked(g, o, seqs, n_out, tag):
     return go
 
 
-@pytest.mark.parametrize("name,sample,eagle2", [("cfg1", 1, False), ("cfg2", 1, True), ("cfg3", 1, False), ("cfg4", 6, False),
-                                                ("cfg4", 4, True)])
+@pytest.mark.parametrize("name,sample,eagle2", [("cfg1", 1, False), ("cfg2", 1, True), ("cfg3", 1, False), ("cfg4", 64, False),
+                                                ("cfg4", 64, True), ("cfg5", 256, False), ("cfg5", 48, True)])
 def test_reranked_finalize_against_oracle(name, sample, eagle2):
     # Sec. 2.2, EAGLE-2's reranking phase over every scored candidate.  eagle2: the classifier is the
     # joint probability itself and beta = 0, i.e. EAGLE-2's own expansion and rerank.
@@ -142,13 +136,63 @@ def test_reranked_finalize_against_oracle(name, sample, eagle2):
         x = layers(l)
         g.expand_layer(x)
         if o.frontier()["n_frontier"].sum() > 0:
-            o.expand_layer(W.as_numpy_bits(x[seqs]), threads=4)
+            o.expand_layer(W.as_numpy_bits(x if len(seqs) == cfg["B"] else x[seqs]), threads=ORACLE_THREADS)
         del x
     torch.cuda.synchronize()
     total = int(o.audit()["scored"].max())
     for n_out in sorted({1, 7, min(60, 1024), min(1024, max(1, total // 2)), min(1024, total + 3)}):
         go = _compare_reranked(g, o, seqs, n_out, name)
     print(name, "rerank: scored per sequence up to", total, "; last n_nodes", go["n_nodes"][seqs].tolist())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_first_pruning_is_strict_at_equality(dtype):
+    # Algorithm 1 keeps C_i > beta: a candidate whose classifier logit EQUALS logit(beta) is dropped.
+    # Zero weights give z = b2 for every candidate.
+    cfg = dict(idx=98, B=3, V=2003, dtype=dtype, D=3, F=4, K=4, h=4, beta=0.5, N=20,
+               zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="equality at the threshold")
+    zero = (np.zeros((4, 3), np.float32), np.zeros(4, np.float32), np.zeros(4, np.float32))
+    layers = _layers(cfg, "eq")
+    go, oo, _ = run_both(cfg, zero + (0.0,), layers, tag="z == logit(beta)")
+    assert (go["n_nodes"] == 0).all() and (oo["n_nodes"] == 0).all()
+    up = float(np.nextafter(np.float32(0), np.float32(1)))
+    go, oo, _ = run_both(cfg, zero + (up,), layers, tag="z one ulp above logit(beta)")
+    assert (go["n_nodes"] == 4 + 2 * 4).all()
+    go, oo, _ = run_both(cfg, zero + (-up,), layers, tag="z one ulp below logit(beta)")
+    assert (go["n_nodes"] == 0).all()
+    cfg3 = dict(cfg, beta=0.3)
+    from oracle import ref_logit_of_beta
+    zb = np.float32(ref_logit_of_beta(0.3))
+    go, oo, _ = run_both(cfg3, zero + (float(zb),), layers, tag="z == logit(0.3)")
+    assert (go["n_nodes"] == 0).all()
+    go, oo, _ = run_both(cfg3, zero + (float(np.nextafter(zb, np.float32(1))),), layers, tag="z above logit(0.3)")
+    assert (go["n_nodes"] > 0).all()
+
+
+def test_reranked_finalize_with_whole_families_tied():
+    # a classifier that grows with the depth: most children score above their parent, so their path
+    # minimum equals the parent's and the reranking is decided by its tie rules (depth, then scoring order)
+    from _harness import make_oracle
+    cfg = dict(idx=99, B=6, V=3001, dtype="bf16", D=5, F=8, K=8, h=2, beta=0.3, N=40, rerank=1,
+               zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="rerank ties")
+    W1 = np.zeros((2, 3), np.float32); W1[0] = (0.4, 0.0, 0.75); W1[1] = (-1.0, 0.1, 0.0)
+    cls = (W1, np.array([0.1, 0.3], np.float32), np.array([1.0, -0.7], np.float32), -0.5)
+    layers = _layers(cfg, "rerank_ties")
+    g = make_gpu(cfg, cls)
+    o = make_oracle(cfg, cls)
+    g.reset(); o.reset()
+    for l in range(cfg["D"]):
+        x = layers(l)
+        g.expand_layer(x)
+        if o.frontier()["n_frontier"].sum() > 0:
+            o.expand_layer(W.as_numpy_bits(x), threads=4)
+    torch.cuda.synchronize()
+    total = int(o.audit()["scored"].max())
+    everything = o.finalize_rerank(total)
+    s = everything["path_min_z"][0, :int(everything["n_nodes"][0])]
+    assert (np.diff(s) == 0).sum() > 20, "the classifier is meant to tie whole families"
+    for n_out in (1, 9, total // 3, total // 2, total, min(1024, total + 5)):
+        _compare_reranked(g, o, list(range(cfg["B"])), n_out, "rerank ties")
 
 
 def test_batched_chain_mode_ragged_lengths():

@@ -195,6 +195,104 @@ def test_rerank_selection_is_a_tree_for_any_classifier():
             np.testing.assert_array_equal(out["tokens"][0, :n], everything["tokens"][0, :n])
 
 
+def _independent_rerank(layers_dump, F, N, zb):
+    """Every scored candidate of a draft phase, rebuilt from the per-layer candidate dumps alone
+    (z, token, slot in scoring order), with its parent and s = smallest z on its path, and the
+    frontier of each layer re-derived with python's sort.  Returns the candidates in the order of
+    Sec. 2.2's reranking as this build reads it: (s desc, depth asc, scoring order asc)."""
+    cands = []                 # dict(idx, depth, token, z, s, parent)
+    frontier = [-1]            # history index of the node in each frontier slot; -1 = root
+    n_nodes = 0
+    for depth, c in enumerate(layers_dump):
+        base = len(cands)
+        for i in range(len(c["z"])):
+            par = frontier[int(c["slot"][i])]
+            z = float(c["z"][i])
+            cands.append(dict(idx=base + i, depth=depth, token=int(c["token"][i]), z=z, parent=par,
+                              s=z if par < 0 else min(cands[par]["s"], z), slot=int(c["slot"][i])))
+        layer = cands[base:]
+        surv = sorted((q for q in layer if q["z"] > zb), key=lambda q: (-q["z"], q["token"], q["slot"]))
+        keep = surv[:max(0, min(F, N - n_nodes))]
+        n_nodes += len(keep)
+        frontier = [q["idx"] for q in keep]
+        if not frontier:
+            break
+    return sorted(cands, key=lambda q: (-q["s"], q["depth"], q["idx"]))
+
+
+def test_rerank_tie_order_against_an_independent_sort():
+    # Sec. 2.2's reranking with a classifier that is NOT monotone along paths and grows with depth:
+    # most children score above their parent, so their path minimum s equals the parent's and whole
+    # families tie in s.  The order among equal s (depth first, then scoring order) is checked against
+    # python's sort over the candidate dumps, not against the oracle's own full ranking.
+    rng = np.random.default_rng(29)
+    V, F, K, D, h, N = 80, 4, 3, 5, 2, 100
+    ties_seen = 0
+    for trial in range(8):
+        logits = random_logits(rng, D, F, V)
+        W1 = np.zeros((h, 3), f32); W1[0] = (0.5 * rng.standard_normal(), 0.0, 0.75)      # z rises with the depth
+        W1[1] = (-1.0, 0.1, 0.0)
+        cls = (W1, np.array([0.1, 0.3], f32), np.array([1.0, float(rng.standard_normal())], f32), f32(-0.5))
+        beta = 0.3
+        t = RefTree(1, V, F, K, D, N, h, 0, beta)
+        t.set_classifier(*cls)
+        t.reset()
+        dumps = []
+        for l in range(D):
+            if t.frontier()["n_frontier"].sum() == 0:
+                break
+            t.expand_layer(logits[l])
+            c = t.candidates()
+            n = int(c["n_cand"][0])
+            dumps.append({k: c[k][0, :n].copy() for k in ("z", "token", "slot")})
+        want_all = _independent_rerank(dumps, F, N, ref_logit_of_beta(beta))
+        total = len(want_all)
+        assert total == int(t.audit()["scored"][0])
+        s_all = [q["s"] for q in want_all]
+        ties_seen += sum(1 for a, b in zip(s_all, s_all[1:]) if a == b)
+        for n_out in (1, 4, total // 3, total // 2, total, total + 2):
+            out = t.finalize_rerank(n_out)
+            want = want_all[:n_out]
+            n = int(out["n_nodes"][0])
+            assert n == len(want)
+            np.testing.assert_array_equal(out["tokens"][0, :n], [q["token"] for q in want])
+            np.testing.assert_array_equal(out["position"][0, :n], [q["depth"] + 1 for q in want])
+            np.testing.assert_array_equal(out["path_min_z"][0, :n], np.array([q["s"] for q in want], f32))
+            pos = {q["idx"]: i for i, q in enumerate(want)}
+            np.testing.assert_array_equal(out["parent"][0, :n], [-1 if q["parent"] < 0 else pos[q["parent"]] for q in want])
+    assert ties_seen > 50, "the classifier is meant to produce many equal path minima"
+
+
+def test_first_pruning_is_strict_at_equality():
+    # Algorithm 1: the loop runs while C_i > beta and removes C_i < beta; at C_i == beta this build
+    # drops the node (strict '>').  All-zero weights give z = b2 for every candidate: with b2 = 0 and
+    # beta = 0.5, z == logit(beta) == 0 exactly and the tree stays empty; one ulp above, everything passes.
+    rng = np.random.default_rng(30)
+    V, F, K, D, h, N = 50, 3, 4, 3, 2, 20
+    logits = random_logits(rng, D, F, V)
+    zero = (np.zeros((h, 3), f32), np.zeros(h, f32), np.zeros(h, f32))
+    t = RefTree(1, V, F, K, D, N, h, 0, 0.5)
+    t.set_classifier(*zero, 0.0)
+    t.reset()
+    t.expand_layer(logits[0])
+    c = t.candidates()
+    assert c["n_cand"][0] == K and (c["z"][0, :K] == 0.0).all() and not c["kept"][0].any()
+    assert t.frontier()["n_frontier"][0] == 0
+    assert t.finalize()["n_nodes"][0] == 0
+    t.set_classifier(*zero, float(np.nextafter(f32(0), f32(1))))
+    out = run(t, logits)
+    assert out["n_nodes"][0] == min(F, K) + (D - 1) * F        # every layer keeps max_frontier nodes
+    t.set_classifier(*zero, float(np.nextafter(f32(0), f32(-1))))
+    assert run(t, logits)["n_nodes"][0] == 0
+    # a threshold other than 0.5: z equal to the rounded logit(beta) is dropped as well
+    zb = ref_logit_of_beta(0.3)
+    t = RefTree(1, V, F, K, D, N, h, 0, 0.3)
+    t.set_classifier(*zero, float(zb))
+    assert run(t, logits)["n_nodes"][0] == 0
+    t.set_classifier(*zero, float(np.nextafter(f32(zb), f32(1))))
+    assert run(t, logits)["n_nodes"][0] > 0
+
+
 def test_candidate_count_matches_paper_tree_size():
     # Appendix B.1: K = 10, d_max = 11 gives complete trees of 1011 nodes = root + K + (d_max-1)*K*K
     g = GOLD["training_tree"]

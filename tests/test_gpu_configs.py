@@ -149,7 +149,7 @@ def test_reranked_finalize_against_oracle(name, sample, eagle2):
 def test_first_pruning_is_strict_at_equality(dtype):
     # Algorithm 1 keeps C_i > beta: a candidate whose classifier logit EQUALS logit(beta) is dropped.
     # Zero weights give z = b2 for every candidate.
-    cfg = dict(idx=98, B=3, V=2003, dtype=dtype, D=3, F=4, K=4, h=4, beta=0.5, N=20,
+    cfg = dict(idx=98, B=3, V=2008, dtype=dtype, D=3, F=4, K=4, h=4, beta=0.5, N=20,
                zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="equality at the threshold")
     zero = (np.zeros((4, 3), np.float32), np.zeros(4, np.float32), np.zeros(4, np.float32))
     layers = _layers(cfg, "eq")
@@ -173,7 +173,7 @@ def test_reranked_finalize_with_whole_families_tied():
     # a classifier that grows with the depth: most children score above their parent, so their path
     # minimum equals the parent's and the reranking is decided by its tie rules (depth, then scoring order)
     from _harness import make_oracle
-    cfg = dict(idx=99, B=6, V=3001, dtype="bf16", D=5, F=8, K=8, h=2, beta=0.3, N=40, rerank=1,
+    cfg = dict(idx=99, B=6, V=3000, dtype="bf16", D=5, F=8, K=8, h=2, beta=0.3, N=40, rerank=1,
                zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="rerank ties")
     W1 = np.zeros((2, 3), np.float32); W1[0] = (0.4, 0.0, 0.75); W1[1] = (-1.0, 0.1, 0.0)
     cls = (W1, np.array([0.1, 0.3], np.float32), np.array([1.0, -0.7], np.float32), -0.5)

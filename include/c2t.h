@@ -161,6 +161,20 @@ int c2t_finalize_tree(c2t_ctx* ctx, const c2t_tree_out* out, void* stream);
  * selection order.  Same place in the call order as c2t_finalize_tree. */
 int c2t_finalize_tree_reranked(c2t_ctx* ctx, const c2t_tree_out* out, int32_t n_out, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace slice for scratch (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * reranking as c2t_finalize_tree_reranked, same arguments, same results, but the kernel's scratch
+ * (one int32 per history entry, batch * max_depth * max_frontier * top_k of them) lives in a static
+ * device array inside the library instead of the context's workspace.  The call allocates nothing
+ * and frees nothing.  Limit: at most C2T_STATIC_RERANK_ENTRIES history entries, else
+ * C2T_ERR_UNSUPPORTED; C2T_ERR_HIP if the array's device address cannot be obtained.  Every call on
+ * one GPU, from any context, uses that GPU's one array: calls that overlap on a GPU (different
+ * streams, or graphs replayed concurrently) race and must be serialised by the caller; calls on
+ * different GPUs are independent.  Nothing needs clearing between calls: the kernel writes every
+ * scratch entry before it reads it. */
+#define C2T_STATIC_RERANK_ENTRIES (4 * 1024 * 1024)   /* 16 MiB of device memory per GPU, held until the process ends */
+int c2t_finalize_tree_reranked_static(c2t_ctx* ctx, const c2t_tree_out* out, int32_t n_out, void* stream);
+
 /* Per-launch accounting for benchmarks: [device] pointer to int32 [max_depth + 1];
  * entry l = number of logits rows layer l's expand consumed (sum over sequences of
  * n_frontier), filled as the layers run. */

@@ -75,6 +75,7 @@ def load_library():
     L.c2t_get_candidates.argtypes = [vp] + [P(vp)] * 7
     L.c2t_finalize_tree.argtypes = [vp, P(_TreeOut), vp]
     L.c2t_finalize_tree_reranked.argtypes = [vp, P(_TreeOut), i32, vp]
+    L.c2t_finalize_tree_reranked_static.argtypes = [vp, P(_TreeOut), i32, vp]
     L.c2t_get_layer_rows.argtypes = [vp, P(vp)]
     L.c2t_set_row_splits.argtypes = [vp, i32, i32]
     L.c2t_profile_enable.argtypes = [vp, i32]
@@ -201,6 +202,15 @@ class C2TContext:
                        ("tokens", "parent", "position", "conf", "joint_prob", "entropy", "n_nodes", "mask", "status")])
         _check(self.L.c2t_finalize_tree_reranked(self.ctx, ctypes.byref(o), int(n_out), _stream_ptr(stream)),
                "c2t_finalize_tree_reranked")
+        return out
+
+    def finalize_tree_reranked_static(self, n_out, out=None, stream=None):
+        """The same reranking with the kernel's scratch in the library's static device array (no allocation)."""
+        out = self.new_tree_out(n_out) if out is None else out
+        o = _TreeOut(*[out[k].data_ptr() for k in
+                       ("tokens", "parent", "position", "conf", "joint_prob", "entropy", "n_nodes", "mask", "status")])
+        _check(self.L.c2t_finalize_tree_reranked_static(self.ctx, ctypes.byref(o), int(n_out), _stream_ptr(stream)),
+               "c2t_finalize_tree_reranked_static")
         return out
 
     def layer_rows(self):

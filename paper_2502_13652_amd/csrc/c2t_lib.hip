@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -18,6 +19,8 @@
 #include "k_tree.h"
 
 using namespace c2t;
+
+static __device__ __align__(256) int32_t scratch[C2T_STATIC_RERANK_ENTRIES];   // see scratch_on_current_device
 
 namespace {
 
@@ -105,6 +108,27 @@ Layout make_layout(const c2t_config& c) {
   }
   L.total = o;
   return L;
+}
+
+// Scratch of c2t_finalize_tree_reranked_static: the reranking's position array (one int per history
+// entry, [B][D*F*K]) in a file-scope device array instead of the caller's workspace.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the array's name is only
+// a stand-in: its device address is asked for once per device (with that device current) and kept.
+constexpr int MAX_DEVICES = 64;
+std::atomic<int32_t*> scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device; nullptr (and *err set) if it cannot be had.
+int32_t* scratch_on_current_device(hipError_t* err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { if (err) *err = e != hipSuccess ? e : hipErrorInvalidDevice; return nullptr; }
+  int32_t* p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  void* sym = nullptr;
+  e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !sym) { if (err) *err = e != hipSuccess ? e : hipErrorInvalidSymbol; return nullptr; }
+  scratch_ptr[dev].store((int32_t*)sym, std::memory_order_release);   // two threads racing here store the same address
+  return (int32_t*)sym;
 }
 
 }  // namespace
@@ -258,6 +282,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
       n = 256;                                                // no device (host-only checks of the interface): MI355X's count
     x->n_cus = n;
   }
+  if (cfg->rerank) (void)scratch_on_current_device(nullptr);    // set-up of the allocation-free reranking; asked again at its first call if there is no device yet
   x->ns_first = default_split(*cfg, L, cfg->batch);
   x->ns_other = default_split(*cfg, L, (int64_t)cfg->batch * cfg->max_frontier);
   *out = x;
@@ -365,6 +390,29 @@ int c2t_finalize_tree_reranked(c2t_ctx* x, const c2t_tree_out* o, int32_t n_out,
   if (!x->cfg.rerank || x->layer < 0) return C2T_ERR_STATE;
   TreeOut t{o->tokens, o->parent, o->position, o->conf, o->joint_prob, o->entropy, o->n_nodes, o->mask, o->status};
   hipLaunchKernelGGL(k_finalize_rerank, dim3(x->cfg.batch), dim3(RR_NT), 0, (hipStream_t)stream, x->st, t, n_out,
+                     x->cfg.max_depth, x->cfg.max_frontier * x->cfg.top_k);
+  if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  x->finalized = true;
+  return C2T_OK;
+}
+
+int c2t_finalize_tree_reranked_static(c2t_ctx* x, const c2t_tree_out* o, int32_t n_out, void* stream) {
+  if (!x || !o) return C2T_ERR_INVALID_ARG;
+  if (!o->tokens || !o->parent || !o->position || !o->conf || !o->joint_prob || !o->entropy || !o->n_nodes ||
+      !o->mask || !o->status)
+    return C2T_ERR_INVALID_ARG;
+  if (n_out <= 0) return C2T_ERR_INVALID_ARG;
+  if (n_out > C2T_MAX_BUDGET) return C2T_ERR_UNSUPPORTED;
+  if (!x->cfg.rerank || x->layer < 0) return C2T_ERR_STATE;
+  const int64_t entries = (int64_t)x->cfg.batch * x->cfg.max_depth * x->cfg.max_frontier * x->cfg.top_k;
+  if (entries > C2T_STATIC_RERANK_ENTRIES) return C2T_ERR_UNSUPPORTED;    // the static array is that large and no larger
+  hipError_t e = hipSuccess;
+  int32_t* pos = scratch_on_current_device(&e);
+  if (!pos) return C2T_ERR_HIP;
+  TreeState st = x->st;
+  st.h_pos = pos;                                             // every entry the kernel reads it has written in the same launch: nothing to clear
+  TreeOut t{o->tokens, o->parent, o->position, o->conf, o->joint_prob, o->entropy, o->n_nodes, o->mask, o->status};
+  hipLaunchKernelGGL(k_finalize_rerank, dim3(x->cfg.batch), dim3(RR_NT), 0, (hipStream_t)stream, st, t, n_out,
                      x->cfg.max_depth, x->cfg.max_frontier * x->cfg.top_k);
   if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
   x->finalized = true;

@@ -30,6 +30,10 @@ static_assert(C2T_MAX_BUDGET == C2T_MAX_BUDGET_DEV && C2T_MAX_CANDIDATES == C2T_
 // Cell map of one workgroup.  bf16: four workgroups of 512 threads share the CU's 160 KB, each with the
 // 16 KB histogram, its static LDS (under 8 KB) and the map (2 bytes per 4 chunks): 16 KB at most.
 constexpr int HP_NT = 512;                     // workgroup size of the histogram kernel
+#ifndef C2T_HP_REPL_ALONE
+#define C2T_HP_REPL_ALONE 4
+#endif
+constexpr int HP_REPL_ALONE = C2T_HP_REPL_ALONE;   // histogram copies of a workgroup that has its CU to itself (launches of at most one workgroup per CU)
 constexpr int MAX_MAP_BYTES_BF16 = 16 * 1024;
 constexpr int MAX_MAP_BYTES_F32 = 48 * 1024;
 constexpr int NT_F32 = 256;                    // workgroup size of the generic kernel for fp32 logits
@@ -190,7 +194,10 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
                 c.batch <= COMPACT_MAX_B) ? 1 : 0;
   sp.h = c.hidden; sp.layer = x->layer; sp.z_beta = x->z_beta; sp.M = c.entropy_top_m; sp.D = c.max_depth;
   if (c.logits_dtype == C2T_BF16) {
-    const size_t lds_work = (std::max(std::max((size_t)HP_WORDS * 4 + map_lds, list_lds), score_lds) + 15) / 16 * 16;
+    const int64_t cus = x->n_cus;
+    const bool four_per_cu = (int64_t)grid > cus;
+    const int repl = four_per_cu ? 1 : HP_REPL_ALONE;       // copies of the histogram in LDS
+    const size_t lds_work = (std::max(std::max((size_t)HP_WORDS * 4 * repl + map_lds, list_lds), score_lds) + 15) / 16 * 16;
     sp.lds_bytes = (int)lds_work;
     sp.w_lds_off = (int)lds_work;                           // behind it: the classifier's parameters, padded to 16 bytes
     const size_t lds = lds_work + ((size_t)(5 * c.hidden + 1) * 4 + 15) / 16 * 16;
@@ -200,21 +207,19 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
     // 256 rows 32.4 / 31.6, 512: 38.8 / 39.8, 1024: 61.0 / 73.1, 1280: 82.7 / 86.6, 1536: 95.3 / 91.6,
     // 2048: 114 / 120, 3072: 166 / 163, 4096: 209 / 215, 8192: 388 / 393.  Four per CU whenever a CU
     // gets more than one workgroup; a workgroup that is alone on its CU is 2-3 % faster on 80 registers.
-    const int64_t cus = x->n_cus;
-    const bool four_per_cu = (int64_t)grid > cus;
-    const void* fn = topm ? (four_per_cu ? (const void*)k_logits_hist<HP_NT, true, 8> : (const void*)k_logits_hist<HP_NT, true, 6>)
-                          : (four_per_cu ? (const void*)k_logits_hist<HP_NT, false, 8> : (const void*)k_logits_hist<HP_NT, false, 6>);
+    const void* fn = topm ? (four_per_cu ? (const void*)k_logits_hist<HP_NT, true, 8, 1> : (const void*)k_logits_hist<HP_NT, true, 6, HP_REPL_ALONE>)
+                          : (four_per_cu ? (const void*)k_logits_hist<HP_NT, false, 8, 1> : (const void*)k_logits_hist<HP_NT, false, 6, HP_REPL_ALONE>);
     size_t& raised = x->lds_raised[four_per_cu ? 1 : 0];
     if (lds > raised) {                                     // beyond the 48 KB a kernel may use without asking
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
       raised = lds;
     }
-#define C2T_LAUNCH_HIST(TOPM, WPS)                                                                                      \
-  hipExtLaunchKernelGGL((k_logits_hist<HP_NT, TOPM, WPS>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride, \
+#define C2T_LAUNCH_HIST(TOPM, WPS, REPL)                                                                                      \
+  hipExtLaunchKernelGGL((k_logits_hist<HP_NT, TOPM, WPS, REPL>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride, \
                         c.vocab, cps, (const double*)x->tab_e, (const float*)x->st.cls, x->st, sp)
-    if (topm) { if (four_per_cu) C2T_LAUNCH_HIST(true, 8); else C2T_LAUNCH_HIST(true, 6); }
-    else      { if (four_per_cu) C2T_LAUNCH_HIST(false, 8); else C2T_LAUNCH_HIST(false, 6); }
+    if (topm) { if (four_per_cu) C2T_LAUNCH_HIST(true, 8, 1); else C2T_LAUNCH_HIST(true, 6, HP_REPL_ALONE); }
+    else      { if (four_per_cu) C2T_LAUNCH_HIST(false, 8, 1); else C2T_LAUNCH_HIST(false, 6, HP_REPL_ALONE); }
 #undef C2T_LAUNCH_HIST
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);

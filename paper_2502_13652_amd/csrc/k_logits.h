@@ -866,7 +866,7 @@ __device__ __forceinline__ void store_classifier(const ClassifierStage& c) {
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
 // TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
 // default kernel carries none of its registers).
-template <int NT, bool TOPM, int WPS>
+template <int NT, bool TOPM, int WPS, int REPL>
 __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
                                              unsigned char* map_lds, const SelectLds& sel, RowResult* rr,
@@ -887,7 +887,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   const int lane = tid & (WAVE - 1), wid = tid >> 6;
 
 #pragma unroll
-  for (int j = 0; j < WPL; ++j) hist[tid + j * NT] = 0u;
+  for (int j = 0; j < WPL * REPL; ++j) hist[tid + j * NT] = 0u;
   if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_out.s_tiny = 0.0; sh_out.n_tiny = 0; sh_out.n_masked = 0; sh_out.mag_max = 0u; }
   __syncthreads();
 
@@ -914,7 +914,12 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     const uint32_t vo = (uint32_t)tid * 16u;
     uint32_t so = 0u;
 #define C2T_LOAD(k) load_stream_buffer(rs, vo, so + (uint32_t)(k) * (NT * 16u))
-#define C2T_COUNT(q) hist_chunk(q, M2, hist, &sh_out)
+    // REPL copies of the histogram, a lane counting into copy (lane mod REPL): neighbouring lanes that
+    // hold the same value (common: few hundred values carry most of a row) then add to different
+    // words, which the LDS does not have to serialise.  The copies are folded after the loop.
+    static_assert(REPL == 1 || REPL == 2 || REPL == 4 || REPL == 8, "a lane picks its copy with a mask");
+    uint32_t* __restrict__ histl = hist + (REPL > 1 ? (tid & (REPL - 1)) * HP_WORDS : 0);
+#define C2T_COUNT(q) hist_chunk(q, M2, histl, &sh_out)
     uint4 q[DEPTH];
 #pragma unroll
     for (int k = 0; k < DEPTH; ++k) q[k] = C2T_LOAD(k);
@@ -986,6 +991,18 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   int lane_pos = 0, lane_neg = 0;
   float vtop = -INFINITY;                               // value of the lane's highest non-empty bin
   const uint32_t w0 = ((uint32_t)(WPL * tid) + HP_WORD_ROT) & (HP_WORDS - 1);   // the lane's words; WPL-aligned: no wrap inside
+  if (REPL > 1) {                                       // fold the copies into the first: only this lane touches these words
+#pragma unroll
+    for (int j = 0; j < WPL; j += 4) {
+      uint4 t = *(const uint4*)(hist + w0 + j);
+#pragma unroll
+      for (int r = 1; r < REPL; ++r) {
+        const uint4 u = *(const uint4*)(hist + r * HP_WORDS + w0 + j);
+        t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;  // a carry out of a 16-bit half shows in the total, like a counter overflow
+      }
+      *(uint4*)(hist + w0 + j) = t;
+    }
+  }
   {
     // low half: count of +|v_j|, high half: count of -|v_j|.  Not kept beyond the sums: the one or
     // two lanes that need their counts again below read them from LDS again.
@@ -1200,7 +1217,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 // element list and the tail reuse all of it.
 // WPS: waves per SIMD the kernel is built for.  8 = four workgroups per CU on 64 registers a lane;
 // 6 = three workgroups per CU on 80 registers, which needs no spills.
-template <int NT, bool TOPM, int WPS>
+template <int NT, bool TOPM, int WPS, int REPL>
 __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
     const float* __restrict__ cls, TreeState st, ScoreParams sp) {
@@ -1222,7 +1239,7 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
     store_classifier(stage_classifier(cls, sp.h, cst.dst));
     if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; }
   }
-  else hist_segment<NT, TOPM, WPS>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4,
+  else hist_segment<NT, TOPM, WPS, REPL>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4 * REPL,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr, cst);
   finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, cst.dst);
 }

@@ -79,7 +79,6 @@ template <> struct LogitTraits<0> {     // fp32
 // A logits chunk is read once per layer: a non-temporal load keeps the stream from evicting what
 // the workgroups reuse (the e^v table, the classifier) from the L2.
 typedef uint32_t c2t_uint4v __attribute__((ext_vector_type(4)));
-typedef uint32_t c2t_uint4v __attribute__((ext_vector_type(4)));
 // 16 bytes at descriptor base + lane offset + scalar offset, non-temporal; zeros past the descriptor's size
 __device__ __forceinline__ uint4 load_stream_buffer(__amdgpu_buffer_rsrc_t rs, uint32_t lane_off, uint32_t scalar_off) {
   const c2t_uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, scalar_off, 2);
@@ -385,6 +384,25 @@ __device__ __forceinline__ void top_m_sums(const uint4* __restrict__ rowp, const
   block_sum2<NT>(Z, S, red, out);
 }
 
+// A row that was split over several workgroups: the M largest logits of the ROW cannot be told from
+// the splits' own sums, so the workgroup that merged the row goes over the whole row once more
+// (five passes of one workgroup: a rare configuration, fp32 rows of more than 49152 logits or bf16
+// rows of more than 262144, with the entropy over the M largest).  Sums relative to the row maximum.
+template <int DT, int NT>
+__device__ __forceinline__ void top_m_of_split_row(const uint4* __restrict__ rowp, int V, int M, RowResult& rr) {
+  if (M <= 0) return;
+  __shared__ double red_t[2][NT / WAVE], sum_t[2];
+  const bool usable = !(rr.part.flags & 1u) && rr.part.Z > 0.0 && rr.part.ref > -INFINITY && rr.part.ref < INFINITY;
+  if (usable) {
+    constexpr int EPC = LogitTraits<DT>::EPC;
+    const Segment whole = make_segment<EPC>(V, 0, (V + EPC - 1) / EPC);
+    top_m_sums<DT, NT>(rowp, whole, M, (float)rr.part.ref, red_t, sum_t);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) { rr.ZM = usable ? sum_t[0] : 0.0; rr.SM = usable ? sum_t[1] : 0.0; }
+  __syncthreads();
+}
+
 // map_lds: one key per cell.
 template <int DT, int NT, int CPC>
 __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int V, int K, int top_m, const Segment sg,
@@ -609,8 +627,9 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   __shared__ RowResult rr;
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
-  else generic_segment<DT, NT, 1>(rowp, V, K, sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);
-  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, nullptr);    // split records are indexed by launched row
+  else generic_segment<DT, NT, 1>(rowp, V, K, nsplit > 1 ? 0 : sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);   // split rows: see top_m_of_split_row
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, nullptr,     // split records are indexed by launched row
+                   [&](RowResult& r) { top_m_of_split_row<DT, NT>(rowp, V, sp.M, r); });
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1241,7 +1260,8 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
   }
   else hist_segment<NT, TOPM, WPS, REPL>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4 * REPL,
                         make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr, cst);
-  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, cst.dst);
+  finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, cst.dst,
+                   [&](RowResult& r) { if (TOPM) top_m_of_split_row<1, NT>(rowp, V, sp.M, r); });
 }
 
 // Plain streaming read: the practical HBM ceiling.

@@ -57,6 +57,12 @@ __global__ void k_reset(TreeState s, int B, int F, int D) {
   for (int j = i; j < B * F; j += gridDim.x * blockDim.x) s.row_tickets[j] = 0;
 }
 
+// A slice of the classifier's parameters on its way to the workspace as a kernel argument.
+struct ClsChunk { static constexpr int N = 240; float v[N]; };
+__global__ void k_set_classifier(float* __restrict__ cls, int off, int n, ClsChunk c) {
+  if ((int)threadIdx.x < n) cls[off + threadIdx.x] = c.v[threadIdx.x];
+}
+
 // Eq. 3 in fp32: fixed chain of fused multiply-adds, hidden units in ascending order.
 // `w` in global memory: every lane reads the same addresses, so the loads are scalar; but each
 // group of hidden units then waits for its own loads (measured: 1.2-1.4 us for 32 hidden units).
@@ -471,10 +477,12 @@ __device__ __forceinline__ bool last_arrival(int32_t* ticket, int expected) {
 // holds its segment's result.  The workgroup that completes a row scores the row's candidates; the
 // workgroup that completes a sequence's last row prunes and appends.  Both overlap with the other
 // workgroups' streaming, so the whole layer is one launch.
-template <int NT>
+// after_merge(rr): called by the whole workgroup that has merged a split row, before the row is scored
+// (the entropy over the M largest logits of a split row is computed there, over the whole row).
+template <int NT, typename AfterMerge>
 __device__ __forceinline__ void finish_layer(const TreeState& s, const ScoreParams& sp, int b, int f, int nf, int split,
                                              int64_t row_launched, RowResult& rr, unsigned char* lds,
-                                             const float* __restrict__ cls, const float* cls_lds) {
+                                             const float* __restrict__ cls, const float* cls_lds, AfterMerge after_merge) {
   const int tid = threadIdx.x, K = sp.K;
   __syncthreads();                                           // rr is complete
   if (sp.nsplit > 1) {
@@ -483,6 +491,7 @@ __device__ __forceinline__ void finish_layer(const TreeState& s, const ScorePara
     if (tid == 0) st_dev(sp.part + po, rr.part);
     if (!last_arrival(s.row_tickets + (int64_t)b * sp.F + f, sp.nsplit)) return;
     merge_row(sp, row_launched, rr, lds, (size_t)sp.lds_bytes);
+    after_merge(rr);
   }
   score_row(s, sp, b, f, rr, cls, cls_lds);
   if (!last_arrival(s.tickets + b, nf)) return;              // nf: the sequence's frontier size, known since the workgroup started

@@ -44,9 +44,12 @@ def test_config_validation(lib):
                 dict(top_k=5, vocab=4), dict(budget=0), dict(hidden=0)):
         assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**bad)), ctypes.byref(need)) == -1, bad
     for big in (dict(top_k=65, max_frontier=1), dict(max_frontier=65, top_k=1), dict(hidden=257), dict(budget=1025),
-                dict(max_frontier=64, top_k=64), dict(entropy_top_m=1000, vocab=1 << 22)):
+                dict(max_frontier=64, top_k=64)):
         assert lib.c2t_workspace_bytes(ctypes.byref(cfg(**big)), ctypes.byref(need)) == -2, big
     assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=1000)), ctypes.byref(need)) == 0
+    # rows long enough to be split over workgroups may also take the entropy over the M largest logits
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=1000, vocab=1 << 22)), ctypes.byref(need)) == 0
+    assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=1000, vocab=152064, logits_dtype=0)), ctypes.byref(need)) == 0
     assert lib.c2t_workspace_bytes(ctypes.byref(cfg(entropy_top_m=-1)), ctypes.byref(need)) == -1
     # reranking keeps every scored candidate: more workspace, bounded history
     plain = ctypes.c_size_t(); lib.c2t_workspace_bytes(ctypes.byref(cfg()), ctypes.byref(plain))

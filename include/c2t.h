@@ -54,7 +54,8 @@ enum {
   C2T_ERR_UNSUPPORTED = -2, /* misaligned logits / stride, size above a compiled limit */
   C2T_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned (256 B) or too small         */
   C2T_ERR_STATE = -4,       /* call out of order, classifier not set                   */
-  C2T_ERR_HIP = -5          /* a HIP runtime call failed (launch, memcpy)               */
+  C2T_ERR_HIP = -5,         /* a HIP runtime call failed (launch, event)                */
+  C2T_ERR_NOMEM = -6        /* host memory for the context could not be allocated      */
 };
 
 /* Limits compiled into the kernels. */
@@ -77,8 +78,9 @@ typedef struct {
   float beta;           /* 0 <= beta < 1                                              */
   int32_t entropy_top_m; /* 0: entropy over the full vocabulary (Eq. 2, line 1);
                             M > 0: over the M most probable tokens, with the probabilities
-                            of the full softmax (Eq. 2, line 2).  Then a row is never split
-                            over workgroups: C2T_ERR_UNSUPPORTED if the vocabulary needs it */
+                            of the full softmax (Eq. 2, line 2).  Rows that have to be split
+                            over workgroups (fp32 rows of more than 49152 logits, bf16 rows of
+                            more than 262144) are gone over once more by one workgroup for it  */
   int32_t rerank;        /* 1: keep every scored candidate of every layer in the workspace so that
                             c2t_finalize_tree_reranked can be called (max_depth * max_frontier *
                             top_k <= C2T_MAX_HISTORY); 0: only the tree                          */
@@ -112,8 +114,11 @@ int c2t_workspace_bytes(const c2t_config* cfg, size_t* out);
 int c2t_create(const c2t_config* cfg, void* dev_workspace, size_t workspace_bytes, c2t_ctx** out);
 void c2t_destroy(c2t_ctx* ctx);
 
-/* Classifier parameters of Eq. 3, [host] pointers, copied to the workspace on `stream`
- * (the host arrays may be reused once the call returns).  W1 is [h][3] with input order
+/* Classifier parameters of Eq. 3, [host] pointers.  The values travel to the workspace as the
+ * arguments of small kernels enqueued on `stream` (one per 240 floats of the 5h + 1): they are read
+ * before the call returns, so the host arrays may be reused or freed at once, the call never blocks
+ * on the device and never touches pageable memory asynchronously, it orders with the layer kernels
+ * of the same stream like any other launch, and it may be repeated at any time between draft phases.  W1 is [h][3] with input order
  * (P, H, d); b1 [h]; w2 [h]; b2 scalar.  z = b2 + sum_j w2[j] * relu(W1[j].(P,H,d) + b1[j]),
  * evaluated in fp32 as a fixed chain of fused multiply-adds, j ascending. */
 int c2t_set_classifier(c2t_ctx* ctx, const float* W1, const float* b1, const float* w2, float b2,
@@ -182,7 +187,7 @@ int c2t_get_layer_rows(c2t_ctx* ctx, const int32_t** layer_rows);
 
 /* Launch-shape override for experiments: number of workgroups a logits row is split over
  * in the first layer (one row per sequence) and in later layers; 0 = library default.
- * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs, or above 1 with entropy_top_m > 0. */
+ * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs. */
 int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
 
 /* Optional timing of the layer kernel with HIP events attached to each launch on the caller's

@@ -14,7 +14,7 @@ _LIB = os.path.join(_LIB_DIR, "libc2t_hip.so")
 _lib = None
 
 F32, BF16 = 0, 1
-_ERR = {-1: "invalid argument", -2: "unsupported", -3: "workspace", -4: "state", -5: "hip"}
+_ERR = {-1: "invalid argument", -2: "unsupported", -3: "workspace", -4: "state", -5: "hip", -6: "out of host memory"}
 
 HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -187,7 +187,7 @@ class C2TContext:
                     position=torch.empty((B, N), **i32), conf=torch.empty((B, N), **f32),
                     joint_prob=torch.empty((B, N), **f32), entropy=torch.empty((B, N), **f32),
                     n_nodes=torch.empty((B,), **i32), mask=torch.empty((B, N, N), dtype=torch.uint8, device=dev),
-                    status=torch.empty((B,), **i32))
+                    status=torch.empty((B,), **i32).view(torch.uint32))        # a bit field: uint32 as in the header
 
     def finalize_tree(self, out=None, stream=None):
         out = self.new_tree_out() if out is None else out

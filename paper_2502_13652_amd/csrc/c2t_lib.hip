@@ -79,7 +79,6 @@ int check_config(const c2t_config* c) {
       c->budget > C2T_MAX_BUDGET || (int64_t)c->max_frontier * c->top_k > C2T_MAX_CANDIDATES)
     return C2T_ERR_UNSUPPORTED;
   if (c->rerank && (int64_t)c->max_depth * c->max_frontier * c->top_k > C2T_MAX_HISTORY) return C2T_ERR_UNSUPPORTED;
-  if (c->entropy_top_m != 0 && min_splits(*c) > 1) return C2T_ERR_UNSUPPORTED;   // the M largest logits of a row are found by one workgroup
   if ((int64_t)c->batch * c->max_frontier * min_splits(*c) > (1 << 24)) return C2T_ERR_UNSUPPORTED;
   return C2T_OK;
 }
@@ -154,7 +153,6 @@ struct c2t_ctx {
   int n_cus;                   // compute units of the device the context was created on
   // optional event timing of the logits pass
   std::vector<hipEvent_t> ev;
-  std::vector<float> cls_host;
   int ev_used;
   int sample_every, sample_first, phase_no;   // events go to the launches of draft phases sample_first, sample_first + sample_every, ...
 };
@@ -251,7 +249,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   Layout L = make_layout(*cfg);
   if (!ws || ((uintptr_t)ws % ALIGN) != 0 || bytes < L.total) return C2T_ERR_WORKSPACE;
   c2t_ctx* x = new (std::nothrow) c2t_ctx();
-  if (!x) return C2T_ERR_INVALID_ARG;
+  if (!x) return C2T_ERR_NOMEM;
   x->cfg = *cfg; x->lay = L; x->ws = (char*)ws;
   char* w = x->ws;
   TreeState& s = x->st;
@@ -302,15 +300,19 @@ void c2t_destroy(c2t_ctx* x) {
 
 int c2t_set_classifier(c2t_ctx* x, const float* W1, const float* b1, const float* w2, float b2, void* stream) {
   if (!x || !W1 || !b1 || !w2) return C2T_ERR_INVALID_ARG;
-  const int h = x->cfg.hidden;
-  std::vector<float>& buf = x->cls_host;      // lives as long as the context: the copy below is asynchronous
-  buf.resize((size_t)5 * h + 1);
-  std::memcpy(buf.data(), W1, (size_t)3 * h * 4);
-  std::memcpy(buf.data() + 3 * h, b1, (size_t)h * 4);
-  std::memcpy(buf.data() + 4 * h, w2, (size_t)h * 4);
-  buf[5 * h] = b2;
-  if (hipMemcpyAsync(x->st.cls, buf.data(), buf.size() * 4, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
-    return C2T_ERR_HIP;
+  const int h = x->cfg.hidden, total = 5 * h + 1;
+  // The parameters go to the device as kernel arguments, ClsChunk::N floats a launch: the runtime
+  // copies arguments when the launch is enqueued, so nothing refers to host memory afterwards.
+  for (int off = 0; off < total; off += ClsChunk::N) {
+    ClsChunk c;
+    const int n = std::min(ClsChunk::N, total - off);
+    for (int i = 0; i < n; ++i) {
+      const int j = off + i;                                  // layout: W1 [3h] | b1 [h] | w2 [h] | b2
+      c.v[i] = j < 3 * h ? W1[j] : j < 4 * h ? b1[j - 3 * h] : j < 5 * h ? w2[j - 4 * h] : b2;
+    }
+    hipLaunchKernelGGL(k_set_classifier, dim3(1), dim3(ClsChunk::N), 0, (hipStream_t)stream, x->st.cls, off, n, c);
+    if (hipGetLastError() != hipSuccess) return C2T_ERR_HIP;
+  }
   // table of e^v for the bf16 value histogram (device-side fp64 exp), once per context
   if (!x->have_cls && x->cfg.logits_dtype == C2T_BF16) {
     hipLaunchKernelGGL(k_init_exp_table, dim3((HP_TAB_DOUBLES + 255) / 256), dim3(256), 0, (hipStream_t)stream, x->tab_e);
@@ -433,7 +435,6 @@ int c2t_get_layer_rows(c2t_ctx* x, const int32_t** layer_rows) {
 int c2t_set_row_splits(c2t_ctx* x, int32_t first_layer, int32_t other_layers) {
   if (!x || first_layer < 0 || other_layers < 0) return C2T_ERR_INVALID_ARG;
   const c2t_config& c = x->cfg;
-  if (c.entropy_top_m > 0 && (first_layer > 1 || other_layers > 1)) return C2T_ERR_UNSUPPORTED;
   const int nmin = min_splits(c);
   const int nmax_size = std::max(1, chunks_of(c));
   int nf = first_layer ? first_layer : default_split(c, x->lay, c.batch);
@@ -497,6 +498,7 @@ const char* c2t_strerror(int code) {
     case C2T_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case C2T_ERR_STATE: return "call out of order or classifier not set";
     case C2T_ERR_HIP: return "HIP runtime call failed";
+    case C2T_ERR_NOMEM: return "out of host memory";
     default: return "unknown error";
   }
 }

@@ -213,6 +213,15 @@ int c2t_stream_read(const void* dev_ptr, size_t bytes, uint32_t* dev_out, void* 
 int c2t_stream_read_rows(const void* dev_ptr, int32_t rows, size_t row_bytes, size_t row_stride_bytes,
                          uint32_t* dev_out, void* stream);
 
+/* Profiling build only (the library compiled with -DC2T_PHASE_TIMES; paper_2502_13652_amd/phase_times.py
+ * builds and drives it): copies to [host] out, for the first n_workgroups (<= 8192) workgroups of the
+ * layer kernel's launches so far, 16 uint64 each: the 100 MHz wall-clock time at which the workgroup's
+ * first thread last passed each phase boundary (start, end of its own stream, histogram complete, sums,
+ * K-th largest value, cells listed, cells re-read, top K ranked, row scored and handed over, sequence
+ * ticket taken, sequence pruned; unused slots keep their previous value).  Synchronises the device.
+ * The normal build returns C2T_ERR_UNSUPPORTED. */
+int c2t_phase_times_read(uint64_t* out, int32_t n_workgroups);
+
 const char* c2t_strerror(int code);
 
 #ifdef __cplusplus

@@ -55,13 +55,15 @@ def build(verbose=False):
     return _LIB
 
 
-def load_library():
+def load_library(path=None):
+    """Load the built library (once per process).  `path`: another build of it, e.g. the profiling build of
+    phase_times.py; only honoured by the first call."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB):
+    if path is None and not os.path.exists(_LIB):
         build()
-    L = ctypes.CDLL(_LIB)
+    L = ctypes.CDLL(path or _LIB)
     vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     P = ctypes.POINTER
     L.c2t_workspace_bytes.argtypes = [P(C2TConfig), P(sz)]
@@ -83,6 +85,7 @@ def load_library():
     L.c2t_profile_sample.argtypes = [vp, i32, i32]
     L.c2t_stream_read.argtypes = [vp, sz, vp, vp]
     L.c2t_stream_read_rows.argtypes = [vp, i32, sz, sz, vp, vp]
+    L.c2t_phase_times_read.argtypes = [vp, i32]
     L.c2t_strerror.argtypes = [ctypes.c_int]
     L.c2t_strerror.restype = ctypes.c_char_p
     _lib = L

@@ -490,6 +490,17 @@ int c2t_stream_read_rows(const void* p, int32_t rows, size_t row_bytes, size_t r
   return hipGetLastError() == hipSuccess ? C2T_OK : C2T_ERR_HIP;
 }
 
+int c2t_phase_times_read(uint64_t* out, int32_t n_workgroups) {
+#ifdef C2T_PHASE_TIMES
+  if (!out || n_workgroups <= 0 || n_workgroups > PT_WORKGROUPS) return C2T_ERR_INVALID_ARG;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(c2t::c2t_phase_times), (size_t)n_workgroups * PT_SLOTS * 8) != hipSuccess) return C2T_ERR_HIP;
+  return C2T_OK;
+#else
+  (void)out; (void)n_workgroups;
+  return C2T_ERR_UNSUPPORTED;
+#endif
+}
+
 const char* c2t_strerror(int code) {
   switch (code) {
     case C2T_OK: return "ok";

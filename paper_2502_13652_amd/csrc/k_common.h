@@ -7,6 +7,19 @@ namespace c2t {
 
 constexpr int WAVE = 64;
 
+// Optional build (-DC2T_PHASE_TIMES): thread 0 of every workgroup of the layer kernel notes the time
+// (100 MHz wall clock) at which it passes each phase boundary; c2t_phase_times_read copies the notes
+// out.  In the normal build the marks expand to nothing.
+constexpr int PT_WORKGROUPS = 8192, PT_SLOTS = 16;
+enum PhaseMark { PT_START = 0, PT_STREAM_END, PT_HIST_COMPLETE, PT_SUMS, PT_TAU, PT_CELLS_LISTED, PT_CELLS_READ, PT_RANKED,
+                 PT_PUBLISHED, PT_TICKET, PT_PRUNED };
+#ifdef C2T_PHASE_TIMES
+__device__ unsigned long long c2t_phase_times[PT_WORKGROUPS * PT_SLOTS];
+#define C2T_PT(i) do { if (threadIdx.x == 0 && blockIdx.x < c2t::PT_WORKGROUPS) c2t::c2t_phase_times[blockIdx.x * c2t::PT_SLOTS + (i)] = wall_clock64(); } while (0)
+#else
+#define C2T_PT(i) do { } while (0)
+#endif
+
 // Per (row, split) result of the logits pass: Z = sum_j e^(x_j - a), S = sum_j (x_j - ref) e^(x_j - a),
 // both fp64, where ref is the segment's largest logit and the exponent offset a is ref (two-pass
 // path) or 0 (histogram path, whose table holds e^v itself).

@@ -962,6 +962,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       }
     }
     vo_after = vo;
+    C2T_PT(PT_STREAM_END);
     store_classifier(cst);                               // published by the barriers below
     const int g0 = sg.c0 + (int)(vo >> 4) + n_groups * (DEPTH * NT);
     __builtin_amdgcn_s_setprio(0);
@@ -1001,6 +1002,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     if (lane == 0) red_m[wid] = m2;
   }
   __syncthreads();                                     // histogram, cell map and wave results complete
+  C2T_PT(PT_HIST_COMPLETE);
 
   // ---------------- Z = sum n_v e^v and S = sum n_v (v - m) e^v ----------------
   // S is accumulated against the largest value seen so far at each level (lane, wave, workgroup),
@@ -1077,6 +1079,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   if (lane == 0) { red_d[0][wid] = Z; red_d[1][wid] = S; red_v[wid] = vw; }
   if (lane == WAVE - 1) { scan_tmp[0][wid] = incl_p; scan_tmp[1][wid] = incl_n; }
   __syncthreads();
+  C2T_PT(PT_SUMS);
 
   uint32_t m2 = HP_F16_NEG_INF2;
 #pragma unroll
@@ -1134,6 +1137,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     }
   }
   __syncthreads();
+  C2T_PT(PT_TAU);
   // Leave this path (uniformly) if a logit that is not masked lies above the window (|x| >= 2^7, +inf, NaN), if a
   // 16-bit counter overflowed (the total is then off by a multiple of 65535 or 65536), if logits
   // below the window exist and the K-th largest logit is not a positive window value (then they
@@ -1213,6 +1217,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   }
   if (tid == 0) sh_cnt = 0;
   __syncthreads();
+  C2T_PT(PT_CELLS_LISTED);
   int n_cells = sh_ncell;
   const bool ties = n_cells > sel.cell_cap;                  // massive ties at tau: the cells above it, then a tie scan
   if (ties) {
@@ -1222,7 +1227,9 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   }
   collect_cells<1, NT, HP_CPC>(rowp, sg.c0, sg.c1, V, tau, ties, cell_list, n_cells, sel, &sh_cnt);
   if (ties) tie_scan<1, NT>(rowp, sg, V, tau, eq_limit, sel, &sh_cnt, scan_tmp);
+  C2T_PT(PT_CELLS_READ);
   const int n_top = rank_list<NT>(K, sel, &sh_cnt, rr->topv, rr->topi);
+  C2T_PT(PT_RANKED);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = 0.0; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = n_top; r.flags = 0u;
@@ -1250,6 +1257,7 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * 2);
   const Segment sg = make_segment<8>(V, split, cps);
   __shared__ RowResult rr;
+  C2T_PT(PT_START);
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   // The classifier's parameters (5h+1 <= 1281 floats) are copied to LDS for the scoring step: the
   // loads are issued now, four floats a thread, and stored behind the streaming loop.

@@ -494,8 +494,11 @@ __device__ __forceinline__ void finish_layer(const TreeState& s, const ScorePara
     after_merge(rr);
   }
   score_row(s, sp, b, f, rr, cls, cls_lds);
+  C2T_PT(PT_PUBLISHED);
   if (!last_arrival(s.tickets + b, nf)) return;              // nf: the sequence's frontier size, known since the workgroup started
+  C2T_PT(PT_TICKET);
   prune_sequence<NT>(s, sp, b, nf, lds);
+  C2T_PT(PT_PRUNED);
 }
 
 struct TreeOut {

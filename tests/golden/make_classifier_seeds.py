@@ -1,8 +1,10 @@
 """Writes tests/golden/classifier_seeds.json.  Calls only the oracle (never the HIP path).
 
 A random 3->h->1 MLP drawn N(0, 0.5) is often degenerate as a pruning classifier (it keeps
-every candidate or none).  Rule, fixed before any GPU run: for each config take the smallest
-seed s >= 0 for which the oracle, run on the first min(B, 4) sequences of workload instance 0,
+every candidate or none).  Rule (it consults the oracle only, never the HIP path; its part (b) was
+added, and every seed chosen again, once after the first HIP path existed, because seeds chosen by
+(a) alone gave trees that die at the root, and such workloads exercise one layer of the path and
+nothing else): for each config take the smallest seed s >= 0 for which the oracle, run on the first min(B, 4) sequences of workload instance 0,
   (a) lets between 20% and 80% of the second layer's candidates pass the threshold beta, and
   (b) builds, for every one of those sequences, a tree that uses the whole node budget or is still
       growing in the last layer (so the workload exercises every layer, not a tree that dies early).

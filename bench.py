@@ -258,7 +258,7 @@ def main():
                    "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
-                     "kernel": "k_logits_hist<512,false,*>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,256>",
+                     "kernel": "k_logits_hist<512,false,*,*>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,512>",
                      "launches": int(n_sampled * D), "sampled_steps": int(n_sampled),
                      "avg_launch_us": float(k1_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(bytes_layer.mean()),

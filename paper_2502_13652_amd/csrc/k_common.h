@@ -12,7 +12,7 @@ constexpr int WAVE = 64;
 // out.  In the normal build the marks expand to nothing.
 constexpr int PT_WORKGROUPS = 8192, PT_SLOTS = 16;
 enum PhaseMark { PT_START = 0, PT_STREAM_END, PT_HIST_COMPLETE, PT_SUMS, PT_TAU, PT_CELLS_LISTED, PT_CELLS_READ, PT_RANKED,
-                 PT_PUBLISHED, PT_TICKET, PT_PRUNED };
+                 PT_PUBLISHED, PT_TICKET, PT_PRUNED, PT_PRUNE_LOADED, PT_PRUNE_FIRST, PT_PRUNE_PRESELECTED, PT_PRUNE_RANKED };
 #ifdef C2T_PHASE_TIMES
 __device__ unsigned long long c2t_phase_times[PT_WORKGROUPS * PT_SLOTS];
 #define C2T_PT(i) do { if (threadIdx.x == 0 && blockIdx.x < c2t::PT_WORKGROUPS) c2t::c2t_phase_times[blockIdx.x * c2t::PT_SLOTS + (i)] = wall_clock64(); } while (0)

@@ -306,6 +306,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   for (int i = tid; i < PRUNE_HIST_WORDS; i += NT) hist[i] = 0u;
   __syncthreads();
   if (tid < nf && info) atomicOr(&flags_or, (int)info);
+  C2T_PT(PT_PRUNE_LOADED);                                   // (thread 0's own loads have arrived: info is used above)
 
   // ---- first pruning: z > logit(beta) ----
   const int ncand = nf * K;
@@ -323,6 +324,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   }
   wait_vector_memory();                                      // the zeros are written before any thread stores a one
   __syncthreads();
+  C2T_PT(PT_PRUNE_FIRST);
 
   // ---- second pruning + budget: rank survivors by (z desc, token asc, slot asc) ----
   int ns = n_surv;
@@ -372,6 +374,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     __syncthreads();
     ns = n_red;
   }
+  C2T_PT(PT_PRUNE_PRESELECTED);
   if (n_keep > 0) {
     int tshift = 0;
     while (tshift < 4 && (ns << (tshift + 1)) <= NT) ++tshift;
@@ -437,6 +440,7 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     }
   }
   __syncthreads();
+  C2T_PT(PT_PRUNE_RANKED);
   if (tid < n_keep) {
     const int64_t o = (int64_t)b * F + tid;
     s.fr_tok[o] = new_tok[tid]; s.fr_pslot[o] = new_pslot[tid];

@@ -17,7 +17,8 @@ _ROOT = os.path.dirname(_HERE)
 sys.path.insert(0, _ROOT)
 
 MARKS = ["start", "own stream ends", "histogram complete", "sums", "K-th largest known", "cells listed", "cells re-read",
-         "top K ranked", "row scored, handed over", "sequence ticket", "sequence pruned"]
+         "top K ranked", "row scored, handed over", "sequence ticket", "sequence pruned",
+         "  candidates loaded", "  first pruning done", "  preselected", "  ranked and appended"]
 
 
 def build():
@@ -79,7 +80,7 @@ def main():
         if np.all(np.isnan(c)):
             continue
         print("%-26s %8.2f %8.2f %8.2f %6d" % (nm, np.nanmean(c), np.nanmin(c), np.nanmax(c), int(np.sum(~np.isnan(c)))))
-    d = np.diff(us[:, :9], axis=1)
+    d = np.diff(us[:, :9], axis=1)   # the row's own boundaries
     print("mean time between boundaries (start .. handed over):", np.round(np.nanmean(d, axis=0), 2).tolist())
     last = int(np.nanargmax(us[:, 8]))
     print("workgroup that hands its row over last:", np.round(us[last], 2).tolist())
@@ -87,6 +88,9 @@ def main():
     if pr.any():
         print("pruning workgroups (%d): handed over -> ticket %.2f us, ticket -> pruned %.2f us (means)"
               % (int(pr.sum()), np.nanmean(us[pr, 9] - us[pr, 8]), np.nanmean(us[pr, 10] - us[pr, 9])))
+        seq = us[pr][:, [9, 11, 12, 13, 14, 10]]
+        print("  inside the sequence step (ticket, candidates loaded, first pruning, preselected, ranked and appended, frontier stored), mean steps:",
+              np.round(np.nanmean(np.diff(seq, axis=1), axis=0), 2).tolist())
     print("first start -> last boundary: %.2f us" % np.nanmax(us))
 
 

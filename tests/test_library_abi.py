@@ -80,9 +80,19 @@ def test_workspace_and_state_errors(lib):
     assert lib.c2t_get_layer_rows(ctx, None) == -1
     assert lib.c2t_profile_sample(ctx, 0, 0) == -1 and lib.c2t_profile_sample(ctx, 4, 4) == -1
     assert lib.c2t_profile_sample(ctx, 4, 2) == 0 and lib.c2t_profile_sample(None, 1, 0) == -1
+    # the allocation-free reranking: argument and state checks come before anything touches the device
+    from paper_2502_13652_amd.binding import _TreeOut
+    outs = ctypes.byref(_TreeOut(*[0x30000] * 9))
+    assert lib.c2t_finalize_tree_reranked_static(ctx, None, 4, None) == -1
+    assert lib.c2t_finalize_tree_reranked_static(ctx, outs, 0, None) == -1
+    assert lib.c2t_finalize_tree_reranked_static(ctx, outs, 1025, None) == -2
+    assert lib.c2t_finalize_tree_reranked_static(ctx, outs, 4, None) == -4    # not a rerank context, nothing expanded
+    # the phase-time read-out exists only in the profiling build of the library
+    buf = (ctypes.c_uint64 * 16)()
+    assert lib.c2t_phase_times_read(buf, 1) == -2
     lib.c2t_destroy(ctx)
     lib.c2t_destroy(None)
-    assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3)
+    assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3) and b"memory" in lib.c2t_strerror(-6)
 
 
 def test_no_cpu_fallback_and_no_oracle_in_the_product():

@@ -291,6 +291,10 @@ LIMIT_CASES = {
     "max_candidates_f32": (2, 4099, "f32", 3, 64, 32, 16, 0.2, 200),
     "wide_frontier_keep_all": (2, 9000, "bf16", 3, 64, 16, 8, 0.0, 1024),
     "tiny_vocab": (5, 70, "bf16", 4, 8, 8, 4, 0.1, 30),
+    # a vocabulary of one 16-byte chunk or less, and as many children as tokens
+    "one_chunk_vocab_bf16": (3, 8, "bf16", 3, 4, 8, 3, 0.0, 12),
+    "sub_chunk_vocab_bf16": (3, 5, "bf16", 3, 3, 5, 3, 0.0, 9),
+    "sub_chunk_vocab_f32": (3, 3, "f32", 3, 3, 3, 3, 0.0, 9),
     "budget_one": (4, 1000, "f32", 3, 4, 4, 4, 0.0, 1),
     # launches of one round with more workgroups than CUs deal the live rows round the CUs: batch sizes
     # that are not multiples of the wave size, small budgets (frontiers of very different lengths,

@@ -91,6 +91,14 @@ def main():
         seq = us[pr][:, [9, 11, 12, 13, 14, 10]]
         print("  inside the sequence step (ticket, candidates loaded, first pruning, preselected, ranked and appended, frontier stored), mean steps:",
               np.round(np.nanmean(np.diff(seq, axis=1), axis=0), 2).tolist())
+    n_cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    if n_cus < len(us) <= 4 * n_cus and len(us) == nwg:
+        # a launch of one round is placed statically: workgroups w, w + n_cus, w + 2 n_cus, ... share a CU
+        hc = np.full(4 * n_cus, np.nan); hc[:len(us)] = us[:, 2]
+        per_cu = np.nanmax(hc.reshape(4, n_cus), axis=0)
+        print("per CU, when the last of its workgroups has its histogram complete: min %.1f, 10 %% %.1f, median %.1f, 90 %% %.1f, max %.1f us"
+              % (per_cu.min(), np.percentile(per_cu, 10), np.median(per_cu), np.percentile(per_cu, 90), per_cu.max()))
+        print("workgroups still streaming at", ", ".join("%d us: %d" % (t, int((us[:, 2] > t).sum())) for t in range(int(per_cu.min()) - 4, int(per_cu.max()) + 2, 2)))
     print("first start -> last boundary: %.2f us" % np.nanmax(us))
 
 

@@ -734,6 +734,8 @@ struct OutsideAcc {
   int32_t n_tiny;                   // their number
   int32_t n_masked;                 // masked logits (see hp_masked: probability 0, ranked last)
   uint32_t mag_max;                 // largest |code| seen outside the fast path: NaN, inf and |x| >= 2^7 show here
+  uint32_t masked_by_lane[WAVE];    // masked logits again, counted where the rest of their chunk is in the window: lane l of every
+                                    // wavefront adds to word l, in the half a negative value's count goes to (folded into n_masked)
 };
 typedef __attribute__((address_space(3))) OutsideAcc* OutsideAccLds;
 
@@ -766,18 +768,18 @@ __device__ __noinline__ uint32_t hist_chunk_outside(uint4 q, int n_valid, uint32
       dm = pk_max_u16(dm, pk_mad_u16(w2[j], TWO2, BIAS2));
     }
     if (!(dm & 0xE000E000u)) {
-      // the masked logits of all the lanes that are here, counted on the scalar unit; one lane adds them
-      int n_masked = 0;
+      // Every lane issues all eight atomics, as for a chunk inside the window; a masked logit's goes to the
+      // lane's own word of masked_by_lane instead of the histogram (one address select per logit: no
+      // branches, no ballots, and the 64 words lie in 64 different places, so masked logits pile up nowhere).
+      // The stand-in value is negative, so the count lands in the word's upper half.
+      typedef __attribute__((address_space(3))) uint32_t* LdsWords;
+      const LdsWords own = &acc->masked_by_lane[lane_id()], hl = (LdsWords)hist;   // LDS addresses: the selects stay 32-bit, the atomics ds_add
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        n_masked += __builtin_popcountll(__builtin_amdgcn_ballot_w64(inf_lo[j] != 0u)) + __builtin_popcountll(__builtin_amdgcn_ballot_w64(inf_hi[j] != 0u));
-      const uint64_t here = __builtin_amdgcn_ballot_w64(true);
-      if (n_masked && lane_id() == (int)__builtin_ctzll(here))
-        __hip_atomic_fetch_add(&acc->n_masked, n_masked, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {                             // masked lanes stay out of the atomics (no same-address pile-up)
-        if (!inf_hi[j]) atomicAdd(&hist[bits_16_27(w2[j])], hist_increment((int32_t)w2[j] >> 31, 0x10000u));
-        if (!inf_lo[j]) atomicAdd(&hist[w2[j] & (HP_WORDS - 1)], hist_increment(__builtin_amdgcn_sbfe((int32_t)w2[j], 15, 1), 0x10000u));
+      for (int j = 0; j < 4; ++j) {
+        const LdsWords a_hi = inf_hi[j] ? own : hl + bits_16_27(w2[j]);
+        const LdsWords a_lo = inf_lo[j] ? own : hl + (w2[j] & (HP_WORDS - 1));
+        __hip_atomic_fetch_add(a_hi, hist_increment((int32_t)w2[j] >> 31, 0x10000u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(a_lo, hist_increment(__builtin_amdgcn_sbfe((int32_t)w2[j], 15, 1), 0x10000u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
       return pk_max_f16(pk_max_f16(w2[0], w2[1]), pk_max_f16(w2[2], w2[3]));
     }
@@ -908,6 +910,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 #pragma unroll
   for (int j = 0; j < WPL * REPL; ++j) hist[tid + j * NT] = 0u;
   if (tid == 0) { sh_tau_rank = -1; sh_n_gt = 0; sh_ncell = 0; sh_out.s_tiny = 0.0; sh_out.n_tiny = 0; sh_out.n_masked = 0; sh_out.mag_max = 0u; }
+  if (tid < WAVE) sh_out.masked_by_lane[tid] = 0u;
   __syncthreads();
 
   // ---------------- streaming loop: count values, record cell maxima ----------------
@@ -1003,6 +1006,10 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   }
   __syncthreads();                                     // histogram, cell map and wave results complete
   C2T_PT(PT_HIST_COMPLETE);
+  if (wid == NW - 1) {                                  // masked logits counted by lane: folded into the one count (read after the next barrier)
+    const int nm = wave_sum_i((int)(sh_out.masked_by_lane[lane] >> 16));
+    if (lane == 0 && nm) sh_out.n_masked += nm;         // every other addition to it happened before the barrier above
+  }
 
   // ---------------- Z = sum n_v e^v and S = sum n_v (v - m) e^v ----------------
   // S is accumulated against the largest value seen so far at each level (lane, wave, workgroup),

@@ -255,7 +255,8 @@ def main():
                    "arithmetic": "%s logits compared as stored; exact integer value counts; fp64 sums (Z, S, p, H); fp32 classifier" % cfg["dtype"],
                    "entropy_top_m": a.entropy_top_m, "rerank": a.rerank, "mask_frac": a.mask_frac, "hip_graph": bool(a.graph),
                    "profile_every": a.profile_every, "classifier_seed": W.classifier_seed(a.workload),
-                   "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean())},
+                   "nodes_scored_per_step": scored_per_step, "tree_nodes_mean": float(n_nodes.mean()),
+                   "workgroups_per_row": list(ctx.row_workgroups())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "k_logits_hist<512,false,*,*>" if cfg["dtype"] == "bf16" else "k_logits_generic<0,512>",
@@ -288,7 +289,8 @@ def main():
             b2 = r2 * c2["V"] * esz_of(c2)
             s = {"ms_per_step": d2 / st * 1e3, "nodes_scored_per_s": int(r2.sum()) * c2["K"] * st / d2, "steps": st,
                  "rows_per_layer": r2.tolist(), "us_per_layer": [round(float(v), 2) for v in (k2.mean(0) * 1e3)],
-                 "us_per_live_layer_mean": float(k2.mean(0)[live].mean() * 1e3)}
+                 "us_per_live_layer_mean": float(k2.mean(0)[live].mean() * 1e3),
+                 "workgroups_per_row": list(x2.row_workgroups())}     # (first layer, later layers): above 1 on the bf16 path = rows shared by workgroups
             if c2["B"] > 1:
                 s["achieved_gbps"] = float(b2.sum() * k2.shape[0] / (k2.sum() / 1e3) / 1e9)
                 s["frac"] = s["achieved_gbps"] / HBM_PEAK_GBPS

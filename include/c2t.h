@@ -187,8 +187,18 @@ int c2t_get_layer_rows(c2t_ctx* ctx, const int32_t** layer_rows);
 
 /* Launch-shape override for experiments: number of workgroups a logits row is split over
  * in the first layer (one row per sequence) and in later layers; 0 = library default.
- * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs. */
+ * C2T_ERR_UNSUPPORTED below the minimum the vocabulary needs.
+ * By default a launch of few long bf16 rows (at most 128 rows of at least 65,536 logits, e.g. a
+ * single sequence's layer or a batch's first layer) lets several workgroups on otherwise idle CUs
+ * count one row together: they add their histograms up through the workspace before the row's one
+ * epilogue, so the results are those of an unshared row.  A count set here (1 included) is taken
+ * literally and switches that off for the layers it is set for. */
 int c2t_set_row_splits(c2t_ctx* ctx, int32_t first_layer, int32_t other_layers);
+
+/* Workgroups that work on one logits row in the first layer's launch and in the later layers'
+ * launches as the context stands: the split count, or the number of workgroups that share a row
+ * (see c2t_set_row_splits).  [host] outputs; either may be NULL. */
+int c2t_get_row_workgroups(const c2t_ctx* ctx, int32_t* first_layer, int32_t* other_layers);
 
 /* Optional timing of the layer kernel with HIP events attached to each launch on the caller's
  * stream (they take the kernel's own begin and end).  c2t_profile_enable creates `capacity` event

@@ -80,6 +80,7 @@ def load_library(path=None):
     L.c2t_finalize_tree_reranked_static.argtypes = [vp, P(_TreeOut), i32, vp]
     L.c2t_get_layer_rows.argtypes = [vp, P(vp)]
     L.c2t_set_row_splits.argtypes = [vp, i32, i32]
+    L.c2t_get_row_workgroups.argtypes = [vp, P(i32), P(i32)]
     L.c2t_profile_enable.argtypes = [vp, i32]
     L.c2t_profile_read.argtypes = [vp, vp, P(i32)]
     L.c2t_profile_sample.argtypes = [vp, i32, i32]
@@ -223,6 +224,12 @@ class C2TContext:
 
     def set_row_splits(self, first_layer=0, other_layers=0):
         _check(self.L.c2t_set_row_splits(self.ctx, first_layer, other_layers), "c2t_set_row_splits")
+
+    def row_workgroups(self):
+        """(first layer, later layers): workgroups per logits row as the context stands."""
+        a, b = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(self.L.c2t_get_row_workgroups(self.ctx, ctypes.byref(a), ctypes.byref(b)), "c2t_get_row_workgroups")
+        return a.value, b.value
 
     def profile_enable(self, capacity):
         _check(self.L.c2t_profile_enable(self.ctx, capacity), "c2t_profile_enable")

@@ -43,6 +43,20 @@ constexpr int PARTIAL_SLOTS_MIN = 16384;       // (row, split) records the works
 // sequence; the two-pass fp32 path is compute-heavy (an fp64 exp per element) and gains from a few.
 constexpr int TARGET_WORKGROUPS_F32 = 256;
 constexpr int MAX_DEFAULT_SPLITS_F32 = 4;
+// Shared rows on the histogram path (share_row): a launch of few rows, each a workgroup alone on its
+// CU, spreads every row over several CUs instead; the workgroups hand their counts over before
+// the epilogue, so the row still has one epilogue and no merge of lists.
+#ifndef C2T_COOP_MAX_SHARE
+#define C2T_COOP_MAX_SHARE 5
+#endif
+#ifndef C2T_COOP_MIN_GROUPS
+#define C2T_COOP_MIN_GROUPS 4
+#endif
+constexpr int COOP_MAX_WORKGROUPS = 256;       // workgroups of such a launch: one per CU at most
+constexpr int COOP_MAX_ROWS = COOP_MAX_WORKGROUPS / 2;
+constexpr int COOP_MAX_SHARE = C2T_COOP_MAX_SHARE;     // workgroups per row at most
+constexpr int COOP_MIN_GROUPS = C2T_COOP_MIN_GROUPS;   // shortest row that is shared, in groups of HP_CPC sweeps (32 KB)
+constexpr int COOP_GROUP_CHUNKS = HP_CPC * HP_NT;      // segments are whole groups: the row's cell map is then the segments' maps end to end
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -53,6 +67,8 @@ struct Layout {
   size_t t_tok, t_parent, t_depth, t_P, t_H, t_z;
   size_t c_tok, c_p, c_P, c_H, c_z, c_kept;
   size_t part, part_topv, part_topi, tab_e;
+  size_t coop_hist, coop_map, coop_acc;                      // shared rows (bf16 rows whose cell map fits one workgroup's LDS)
+  int coop_map_stride;                                       // keys per row there; 0: no shared rows for this configuration
   size_t total;
   int64_t partial_slots;
 };
@@ -102,6 +118,13 @@ Layout make_layout(const c2t_config& c) {
   L.part_topv = take((size_t)L.partial_slots * K * 4);
   L.part_topi = take((size_t)L.partial_slots * K * 4);
   L.tab_e = take((size_t)HP_TAB_DOUBLES * 8);
+  L.coop_hist = L.coop_map = L.coop_acc = 0; L.coop_map_stride = 0;
+  if (c.logits_dtype == C2T_BF16 && min_splits(c) == 1 && (chunks_of(c) + COOP_GROUP_CHUNKS - 1) / COOP_GROUP_CHUNKS >= COOP_MIN_GROUPS) {
+    L.coop_map_stride = (cells_in_segment<HP_NT, HP_CPC>(chunks_of(c)) + 7) / 8 * 8;
+    L.coop_hist = take((size_t)COOP_MAX_WORKGROUPS * HP_WORDS * 4);
+    L.coop_map = take((size_t)COOP_MAX_ROWS * L.coop_map_stride * 2);
+    L.coop_acc = take((size_t)COOP_MAX_WORKGROUPS * sizeof(CoopAcc));
+  }
   L.fr_hidx = L.fr_s = L.h_tok = L.h_par = L.h_P = L.h_H = L.h_z = L.h_s = L.h_ncand = L.h_pos = 0;
   if (c.rerank) {
     const size_t H = B * (size_t)c.max_depth * F * K * 4;
@@ -149,7 +172,8 @@ struct c2t_ctx {
   int layer;          // layers expanded since reset; -1 before the first reset
   bool have_cls, finalized;
   int ns_first, ns_other;      // row splits in use
-  size_t lds_raised[2];        // dynamic LDS this context has asked the runtime to allow each build of its layer kernel so far
+  bool share_first, share_other;   // rows may be shared by workgroups (the default; off where the caller has set the splits itself)
+  size_t lds_raised[3];        // dynamic LDS this context has asked the runtime to allow each build of its layer kernel so far
   int n_cus;                   // compute units of the device the context was created on
   // optional event timing of the logits pass
   std::vector<hipEvent_t> ev;
@@ -170,22 +194,44 @@ int default_split(const c2t_config& c, const Layout& L, int64_t rows) {
   return (int)std::max<int64_t>(ns, nmin);
 }
 
+// Workgroups that share a row when `rows` rows are launched unsplit; 1: rows are not shared.
+// Every workgroup gets at least one whole group of chunks, and there is at most one workgroup per CU.
+struct Share { int n, groups_each; };
+Share share_of(const c2t_config& c, const Layout& L, int n_cus, int64_t rows) {
+  Share none{1, 0};
+  if (L.coop_map_stride == 0 || rows > COOP_MAX_ROWS) return none;
+  const int groups = (chunks_of(c) + COOP_GROUP_CHUNKS - 1) / COOP_GROUP_CHUNKS;
+  const int64_t workgroups = std::min<int64_t>(n_cus, COOP_MAX_WORKGROUPS);
+  const int n_max = (int)std::min<int64_t>(std::min<int64_t>(workgroups / rows, COOP_MAX_SHARE), groups);
+  if (n_max < 2 || groups < COOP_MIN_GROUPS) return none;
+  Share sh;
+  sh.groups_each = (groups + n_max - 1) / n_max;
+  sh.n = (groups + sh.groups_each - 1) / sh.groups_each;    // the last workgroup's segment starts inside the row
+  return sh.n >= 2 ? sh : none;
+}
+
 // ev0/ev1: optional events attached to the dispatch itself (they take the kernel's own begin and
 // end times, without the launch gap that events recorded around a launch include).
-hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit,
+hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int rows_per_seq, int nsplit, bool may_share,
                          hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const c2t_config& c = x->cfg;
   const int cpc = cpc_of(c);
-  const int cps = (chunks_of(c) + nsplit - 1) / nsplit;
-  const int cells = c.logits_dtype == C2T_BF16 ? cells_in_segment<HP_NT, HP_CPC>(cps) : cps;
+  const Share share = (may_share && nsplit == 1) ? share_of(c, x->lay, x->n_cus, (int64_t)c.batch * rows_per_seq) : Share{1, 0};
+  const int per_row = share.n > 1 ? share.n : nsplit;       // workgroups per row
+  const int cps = share.n > 1 ? share.groups_each * COOP_GROUP_CHUNKS : (chunks_of(c) + nsplit - 1) / nsplit;
+  // the cell map in LDS: the workgroup's segment; the whole row where rows are shared (the workgroup that finishes the row loads it)
+  const int cells = c.logits_dtype == C2T_BF16 ? cells_in_segment<HP_NT, HP_CPC>(share.n > 1 ? chunks_of(c) : cps) : cps;
   const size_t map_lds = ((size_t)cells * keybytes_of(c) + 15) / 16 * 16;
   // element list of the selection: (2K-1) cells of cpc chunks, 8 bytes per element
   const size_t list_lds = (size_t)(2 * c.top_k - 1) * cpc * epc_of(c) * 8;
   const size_t score_lds = score_lds_bytes(c.hidden, c.max_frontier * c.top_k);
-  const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * nsplit);
+  const unsigned grid = (unsigned)((int64_t)c.batch * rows_per_seq * per_row);
   ScoreParams sp;
   sp.part = x->part; sp.part_topv = x->part_topv; sp.part_topi = x->part_topi;
   sp.nsplit = nsplit; sp.rows_per_seq = rows_per_seq; sp.B = c.batch; sp.F = c.max_frontier; sp.K = c.top_k; sp.N = c.budget;
+  sp.coop = share.n; sp.coop_map_stride = x->lay.coop_map_stride;
+  sp.coop_hist = (uint32_t*)(x->ws + x->lay.coop_hist); sp.coop_map = (uint16_t*)(x->ws + x->lay.coop_map);
+  sp.coop_acc = (CoopAcc*)(x->ws + x->lay.coop_acc);
   // one round of workgroups (static placement), more of them than CUs, and few enough sequences:
   // deal the live rows round the CUs
   sp.compact = (rows_per_seq > 1 && (int64_t)grid > (int64_t)x->n_cus && (int64_t)grid <= 4 * (int64_t)x->n_cus &&
@@ -205,19 +251,29 @@ hipError_t launch_logits(c2t_ctx* x, const void* logits, int64_t stride, int row
     // 256 rows 32.4 / 31.6, 512: 38.8 / 39.8, 1024: 61.0 / 73.1, 1280: 82.7 / 86.6, 1536: 95.3 / 91.6,
     // 2048: 114 / 120, 3072: 166 / 163, 4096: 209 / 215, 8192: 388 / 393.  Four per CU whenever a CU
     // gets more than one workgroup; a workgroup that is alone on its CU is 2-3 % faster on 80 registers.
-    const void* fn = topm ? (four_per_cu ? (const void*)k_logits_hist<HP_NT, true, 8, 1> : (const void*)k_logits_hist<HP_NT, true, 6, HP_REPL_ALONE>)
-                          : (four_per_cu ? (const void*)k_logits_hist<HP_NT, false, 8, 1> : (const void*)k_logits_hist<HP_NT, false, 6, HP_REPL_ALONE>);
-    size_t& raised = x->lds_raised[four_per_cu ? 1 : 0];
+    const bool coop = share.n > 1;                           // (never with four per CU: see share_of)
+#define C2T_HIST_KERNEL(TOPM)                                                                                   \
+  (four_per_cu ? (const void*)k_logits_hist<HP_NT, TOPM, 8, 1, false>                                            \
+               : coop ? (const void*)k_logits_hist<HP_NT, TOPM, 6, HP_REPL_ALONE, true> : (const void*)k_logits_hist<HP_NT, TOPM, 6, HP_REPL_ALONE, false>)
+    const void* fn = topm ? C2T_HIST_KERNEL(true) : C2T_HIST_KERNEL(false);
+#undef C2T_HIST_KERNEL
+    size_t& raised = x->lds_raised[four_per_cu ? 1 : coop ? 2 : 0];
     if (lds > raised) {                                     // beyond the 48 KB a kernel may use without asking
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
       raised = lds;
     }
-#define C2T_LAUNCH_HIST(TOPM, WPS, REPL)                                                                                      \
-  hipExtLaunchKernelGGL((k_logits_hist<HP_NT, TOPM, WPS, REPL>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride, \
+#define C2T_LAUNCH_HIST(TOPM, WPS, REPL, COOP)                                                                                      \
+  hipExtLaunchKernelGGL((k_logits_hist<HP_NT, TOPM, WPS, REPL, COOP>), dim3(grid), dim3(HP_NT), lds, s, ev0, ev1, 0, logits, stride, \
                         c.vocab, cps, (const double*)x->tab_e, (const float*)x->st.cls, x->st, sp)
-    if (topm) { if (four_per_cu) C2T_LAUNCH_HIST(true, 8, 1); else C2T_LAUNCH_HIST(true, 6, HP_REPL_ALONE); }
-    else      { if (four_per_cu) C2T_LAUNCH_HIST(false, 8, 1); else C2T_LAUNCH_HIST(false, 6, HP_REPL_ALONE); }
+#define C2T_LAUNCH_HIST_BUILD(TOPM)                                      \
+  do {                                                                   \
+    if (four_per_cu) C2T_LAUNCH_HIST(TOPM, 8, 1, false);                 \
+    else if (coop) C2T_LAUNCH_HIST(TOPM, 6, HP_REPL_ALONE, true);        \
+    else C2T_LAUNCH_HIST(TOPM, 6, HP_REPL_ALONE, false);                 \
+  } while (0)
+    if (topm) C2T_LAUNCH_HIST_BUILD(true); else C2T_LAUNCH_HIST_BUILD(false);
+#undef C2T_LAUNCH_HIST_BUILD
 #undef C2T_LAUNCH_HIST
   } else {
     const size_t lds = std::max(std::max(std::max(map_lds, list_lds), score_lds), (size_t)16 * 1024);
@@ -278,7 +334,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   x->tab_e = (double*)(w + L.tab_e);
   x->z_beta = cfg->beta <= 0.0f ? -INFINITY : (float)std::log((double)cfg->beta / (1.0 - (double)cfg->beta));
   x->layer = -1; x->have_cls = false; x->finalized = false; x->ev_used = 0; x->sample_every = 1; x->sample_first = 0; x->phase_no = -1;
-  x->lds_raised[0] = x->lds_raised[1] = 48 * 1024;
+  x->lds_raised[0] = x->lds_raised[1] = x->lds_raised[2] = 48 * 1024;
   {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
@@ -288,6 +344,7 @@ int c2t_create(const c2t_config* cfg, void* ws, size_t bytes, c2t_ctx** out) {
   if (cfg->rerank) (void)scratch_on_current_device(nullptr);    // set-up of the allocation-free reranking; asked again at its first call if there is no device yet
   x->ns_first = default_split(*cfg, L, cfg->batch);
   x->ns_other = default_split(*cfg, L, (int64_t)cfg->batch * cfg->max_frontier);
+  x->share_first = x->share_other = true;
   *out = x;
   return C2T_OK;
 }
@@ -345,7 +402,7 @@ int c2t_expand_layer(c2t_ctx* x, const void* logits, int64_t row_stride_elems, v
   const int rows_per_seq = first ? 1 : c.max_frontier;
   const int nsplit = first ? x->ns_first : x->ns_other;
   const bool timed = !x->ev.empty() && x->ev_used + 2 <= (int)x->ev.size() && x->phase_no % x->sample_every == x->sample_first;
-  hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, s,
+  hipError_t e = launch_logits(x, logits, row_stride_elems, rows_per_seq, nsplit, first ? x->share_first : x->share_other, s,
                                timed ? x->ev[x->ev_used] : nullptr, timed ? x->ev[x->ev_used + 1] : nullptr);
   if (e != hipSuccess) return C2T_ERR_HIP;
   if (timed) x->ev_used += 2;
@@ -443,6 +500,19 @@ int c2t_set_row_splits(c2t_ctx* x, int32_t first_layer, int32_t other_layers) {
   if ((int64_t)c.batch * nf > x->lay.partial_slots || (int64_t)c.batch * c.max_frontier * no > x->lay.partial_slots)
     return C2T_ERR_WORKSPACE;
   x->ns_first = nf; x->ns_other = no;
+  x->share_first = first_layer == 0; x->share_other = other_layers == 0;   // a split count the caller has set is taken literally
+  return C2T_OK;
+}
+
+int c2t_get_row_workgroups(const c2t_ctx* x, int32_t* first_layer, int32_t* other_layers) {
+  if (!x) return C2T_ERR_INVALID_ARG;
+  const c2t_config& c = x->cfg;
+  auto per_row = [&](int nsplit, bool may_share, int64_t rows) {
+    const Share sh = (may_share && nsplit == 1) ? share_of(c, x->lay, x->n_cus, rows) : Share{1, 0};
+    return sh.n > 1 ? sh.n : nsplit;
+  };
+  if (first_layer) *first_layer = per_row(x->ns_first, x->share_first, c.batch);
+  if (other_layers) *other_layers = per_row(x->ns_other, x->share_other, (int64_t)c.batch * c.max_frontier);
   return C2T_OK;
 }
 

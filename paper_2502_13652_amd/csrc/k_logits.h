@@ -883,15 +883,117 @@ __device__ __forceinline__ void store_classifier(const ClassifierStage& c) {
   if (c.mine) ((float4*)c.dst)[threadIdx.x] = c.q;
 }
 
+// A row shared by sp.coop workgroups (launches that leave most of the chip idle: a single sequence,
+// a root layer).  One workgroup counts a 256 KB row at the rate of its CU's LDS atomics, 9 us; n
+// workgroups on n CUs count a segment each, and their histograms, being sums, merge exactly.  Each
+// hands over through memory what the epilogue needs of its segment: the 4096 count words (copies
+// already folded), the keys of its cells (segments are whole groups of four sweeps, so the row's
+// map is the segments' maps laid end to end) and the few numbers of OutsideAcc.  The stores are
+// device-coherent and complete before the workgroup takes the row's ticket; the workgroup that takes
+// the last one adds the n histograms up in its own LDS, loads the row's map, and goes on as if it
+// had counted the whole row.  The sums, the K-th largest value and the selection therefore come
+// out exactly as for an unshared row (the sum of the logits below the window is added up per
+// segment first: a different rounding order for a term of relative size 1e-16).
+// Every slot is written once and read once per launch: nothing has to be cleared between launches.
+// Returns true in the workgroup that goes on.  map: the segment's keys in LDS, with room for the row's.
+constexpr int COOP_BATCH = 4;                   // other segments whose counts a lane has in flight at once (eight registers each)
+template <int NT>
+__device__ __forceinline__ bool share_row(const ScoreParams& sp, int split, int64_t row_launched, int32_t* row_ticket,
+                                          const Segment& sg, uint32_t* __restrict__ hist, uint32_t w0, uint16_t* map,
+                                          OutsideAcc* sh_out, uint32_t* red_m) {
+  constexpr int NW = NT / WAVE;
+  constexpr uint32_t SLOT_BYTES = HP_WORDS * 4, COHERENT = 16;          // cache policy sc1: served at the device's coherence point
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid >> 6;
+  const int n = sp.coop;
+  const __amdgpu_buffer_rsrc_t rh = __builtin_amdgcn_make_buffer_rsrc((void*)(sp.coop_hist + row_launched * n * HP_WORDS), 0,
+                                                                      n * (int)SLOT_BYTES, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc((void*)(sp.coop_map + row_launched * sp.coop_map_stride), 0,
+                                                                      sp.coop_map_stride * 2, 0x00020000);
+  CoopAcc* const acc = sp.coop_acc + row_launched * n;
+  {
+    const uint4 t0 = *(const uint4*)(hist + w0), t1 = *(const uint4*)(hist + w0 + 4);
+    const c2t_uint4v u0 = {t0.x, t0.y, t0.z, t0.w}, u1 = {t1.x, t1.y, t1.z, t1.w};
+    __builtin_amdgcn_raw_buffer_store_b128(u0, rh, w0 * 4u, (uint32_t)split * SLOT_BYTES, COHERENT);
+    __builtin_amdgcn_raw_buffer_store_b128(u1, rh, w0 * 4u + 16u, (uint32_t)split * SLOT_BYTES, COHERENT);
+    const int ncells = cells_in_segment<NT, HP_CPC>(sg.ncell);
+    const uint32_t first_key_byte = (uint32_t)sg.c0 / HP_CPC * 2u;     // sg.c0 is a multiple of HP_CPC * NT chunks
+    for (int i = tid * 8; i < ncells; i += NT * 8) {                    // (a store that reaches past the row's keys is dropped by the bounds check)
+      const uint4 k = *(const uint4*)(map + i);
+      const c2t_uint4v kv = {k.x, k.y, k.z, k.w};
+      __builtin_amdgcn_raw_buffer_store_b128(kv, rm, (uint32_t)i * 2u, first_key_byte, COHERENT);
+    }
+    if (wid == NW - 1 && lane == 0) {                                   // the lane that has just folded masked_by_lane into n_masked
+      uint32_t m2 = HP_F16_NEG_INF2;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) m2 = pk_max_f16(m2, red_m[w]);
+      CoopAcc* a = acc + split;
+      st_dev(&a->s_tiny, sh_out->s_tiny);
+      st_dev(&a->n_tiny, sh_out->n_tiny); st_dev(&a->n_masked, sh_out->n_masked);
+      st_dev(&a->mag_max, sh_out->mag_max); st_dev(&a->max_pattern, m2);
+    }
+  }
+  wait_vector_memory();                                                 // this wave's stores have reached the coherence point
+  __syncthreads();                                                      // ... and every wave's; the reads of LDS above are done
+  if (!last_arrival(row_ticket, n)) return false;
+
+  // Every load of the first round trip is issued before anything waits: the segments' numbers
+  // (wave 0, one segment per lane), the row's keys (two loads a thread cover the largest map) and the
+  // first COOP_BATCH segments' counts.
+  const bool have = wid == 0 && lane < n;
+  const CoopAcc* a = acc + (have ? lane : 0);
+  double st = 0.0; int nt = 0, nm = 0; uint32_t mm = 0u, mp = HP_F16_NEG_INF2;
+  if (have) { st = ld_dev(&a->s_tiny); nt = ld_dev(&a->n_tiny); nm = ld_dev(&a->n_masked); mm = ld_dev(&a->mag_max); mp = ld_dev(&a->max_pattern); }
+  const int k0 = tid * 8, k1 = k0 + NT * 8;
+  const c2t_uint4v kv0 = __builtin_amdgcn_raw_buffer_load_b128(rm, (uint32_t)k0 * 2u, 0u, COHERENT);   // zeros past the row's keys
+  const c2t_uint4v kv1 = __builtin_amdgcn_raw_buffer_load_b128(rm, (uint32_t)k1 * 2u, 0u, COHERENT);
+  // The other n - 1 segments' counts, from the next segment on round the row; its own are still in LDS.
+  uint4 c0 = *(const uint4*)(hist + w0), c1 = *(const uint4*)(hist + w0 + 4);
+  for (int j0 = 0; j0 < n - 1; j0 += COOP_BATCH) {
+    c2t_uint4v v[2 * COOP_BATCH];
+#pragma unroll
+    for (int j = 0; j < COOP_BATCH; ++j) {
+      int sl = split + 1 + j0 + j;
+      sl = sl >= n ? sl - n : sl;
+      const uint32_t so = (j0 + j < n - 1) ? (uint32_t)sl * SLOT_BYTES : (uint32_t)n * SLOT_BYTES;   // past the last slot: zeros from the bounds check, no traffic
+      v[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(rh, w0 * 4u, so, COHERENT);
+      v[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(rh, w0 * 4u + 16u, so, COHERENT);
+    }
+#pragma unroll
+    for (int j = 0; j < COOP_BATCH; ++j) {                              // a carry out of a 16-bit half shows in the total, like a counter overflow
+      c0.x += v[2 * j].x; c0.y += v[2 * j].y; c0.z += v[2 * j].z; c0.w += v[2 * j].w;
+      c1.x += v[2 * j + 1].x; c1.y += v[2 * j + 1].y; c1.z += v[2 * j + 1].z; c1.w += v[2 * j + 1].w;
+    }
+  }
+  *(uint4*)(hist + w0) = c0; *(uint4*)(hist + w0 + 4) = c1;             // only this lane reads these words before the next barrier
+  if (k0 < sp.coop_map_stride) *(uint4*)(map + k0) = make_uint4(kv0.x, kv0.y, kv0.z, kv0.w);
+  if (k1 < sp.coop_map_stride) *(uint4*)(map + k1) = make_uint4(kv1.x, kv1.y, kv1.z, kv1.w);
+  for (int i = k1 + NT * 8; i < sp.coop_map_stride; i += NT * 8) {      // (longer maps than the launch code allows today)
+    const c2t_uint4v kv = __builtin_amdgcn_raw_buffer_load_b128(rm, (uint32_t)i * 2u, 0u, COHERENT);
+    *(uint4*)(map + i) = make_uint4(kv.x, kv.y, kv.z, kv.w);
+  }
+  if (wid == 0) {                                                       // fixed order of the sums
+    const double st_all = wave_sum(st);
+    const int nt_all = wave_sum_i(nt), nm_all = wave_sum_i(nm);
+    const uint32_t mm_all = wave_reduce_u32(mm, 0u, [](uint32_t x, uint32_t y) { return max(x, y); });
+    const uint32_t mp_all = wave_reduce_u32(mp, HP_F16_NEG_INF2, [](uint32_t x, uint32_t y) { return pk_max_f16(x, y); });
+    if (lane == 0) { sh_out->s_tiny = st_all; sh_out->n_tiny = nt_all; sh_out->n_masked = nm_all; sh_out->mag_max = mm_all; }
+    if (lane < NW) red_m[lane] = mp_all;
+  }
+  return true;                                                          // the caller's next barrier publishes map, sh_out and red_m
+}
+
 // One (row, split) segment on the histogram path, run by a whole workgroup of NT threads.
 // hist: HP_WORDS words; map_lds: one 2-byte key per cell, padded to 16 bytes; sel: see SelectLds.
 // TOPM: built with the entropy over the M largest logits (a separate instantiation, so that the
 // default kernel carries none of its registers).
-template <int NT, bool TOPM, int WPS, int REPL>
-__device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg,
+// COOP: built with the hand-over of a shared row (see share_row); returns false in the workgroups
+// that have handed their segment over and are done, true in the one that holds the row's result.
+template <int NT, bool TOPM, int WPS, int REPL, bool COOP>
+__device__ __forceinline__ bool hist_segment(const uint4* __restrict__ rowp, int V, int K, int M, const Segment& sg_own,
                                              const double* __restrict__ tab_e, uint32_t* __restrict__ hist,
                                              unsigned char* map_lds, const SelectLds& sel, RowResult* rr,
-                                             const ClassifierStage cst) {
+                                             const ClassifierStage cst, const ScoreParams& sp, int split, int64_t row_launched,
+                                             int32_t* row_ticket) {
   constexpr int NW = NT / WAVE;
   constexpr int WPL = HP_WORDS / NT;                   // words per lane in the epilogue (8 at 512 threads)
   static_assert(NW <= 16 && WPL % 4 == 0, "one DPP row holds the per-wave partials; a lane reads whole 16-byte runs");
@@ -906,6 +1008,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 
   int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1), wid = tid >> 6;
+  Segment sg = sg_own;                                   // what the workgroup streams; the whole row once a shared row's counts are merged
 
 #pragma unroll
   for (int j = 0; j < WPL * REPL; ++j) hist[tid + j * NT] = 0u;
@@ -998,7 +1101,9 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
   // The lane owns the magnitude indices WPL*tid .. WPL*tid + WPL-1, with both signs.  The table
   // loads for their e^v are issued now so that their latency hides behind the barrier.
   static_assert(WPL == 8, "a lane's magnitudes share one exponent, one upper fraction and bit 3 of the lower");
-  const ExpFactors ef = load_exp_factors(tab_e, tid);
+  const bool shared_row = COOP && sp.coop > 1;          // (uniform) then the factors are loaded behind the hand-over: they would
+  ExpFactors ef;                                        // only take registers from it
+  if (!shared_row) ef = load_exp_factors(tab_e, tid);
   // per-wave: maximum
   {
     const uint32_t m2 = wave_reduce_u32(M2, HP_F16_NEG_INF2, [](uint32_t x, uint32_t y) { return pk_max_f16(x, y); });
@@ -1030,6 +1135,11 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       }
       *(uint4*)(hist + w0 + j) = t;
     }
+  }
+  if (shared_row) {
+    if (!share_row<NT>(sp, split, row_launched, row_ticket, sg, hist, w0, map, &sh_out, red_m)) return false;
+    sg = make_segment<8>(V, 0, (V + 7) / 8);             // the epilogue below is the whole row's
+    ef = load_exp_factors(tab_e, tid);
   }
   {
     // low half: count of +|v_j|, high half: count of -|v_j|.  Not kept beyond the sums: the one or
@@ -1158,7 +1268,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
       (TOPM && n_tiny > 0 && tot_p < M && M < tot_p + n_tiny)) {
     __syncthreads();
     generic_segment<1, NT, HP_CPC>(rowp, V, K, M, sg, map_lds, sel, rr, 2u);
-    return;
+    return true;
   }
   if (TOPM) {
     // Eq. 2, second line: Z and S restricted to the M largest logits.  A lane's values, from the
@@ -1243,6 +1353,7 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
     rr->part = r;
     if (TOPM) { rr->ZM = sum_m[0]; rr->SM = sum_m[1]; }
   }
+  return true;
 }
 
 // grid: rows_launched * nsplit workgroups of NT threads.
@@ -1250,12 +1361,12 @@ __device__ __forceinline__ void hist_segment(const uint4* __restrict__ rowp, int
 // element list and the tail reuse all of it.
 // WPS: waves per SIMD the kernel is built for.  8 = four workgroups per CU on 64 registers a lane;
 // 6 = three workgroups per CU on 80 registers, which needs no spills.
-template <int NT, bool TOPM, int WPS, int REPL>
+template <int NT, bool TOPM, int WPS, int REPL, bool COOP>
 __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
     const void* __restrict__ logits, int64_t row_stride_elems, int V, int cps, const double* __restrict__ tab_e,
     const float* __restrict__ cls, TreeState st, ScoreParams sp) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  const int nsplit = sp.nsplit, K = sp.K;
+  const int nsplit = (COOP && sp.coop > 1) ? sp.coop : sp.nsplit, K = sp.K;     // workgroups per row, either way
   const int split = blockIdx.x % nsplit;
   const RowOfWorkgroup rw = row_of_workgroup(st, sp, blockIdx.x / nsplit);
   const int b = rw.b, f = rw.f, rl = b * sp.rows_per_seq + f, nf = rw.nf;
@@ -1273,8 +1384,10 @@ __global__ __launch_bounds__(NT, WPS) void k_logits_hist(
     store_classifier(stage_classifier(cls, sp.h, cst.dst));
     if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; }
   }
-  else hist_segment<NT, TOPM, WPS, REPL>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4 * REPL,
-                        make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr, cst);
+  else if (!hist_segment<NT, TOPM, WPS, REPL, COOP>(rowp, V, K, TOPM ? sp.M : 0, sg, tab_e, (uint32_t*)dyn_lds, dyn_lds + HP_WORDS * 4 * REPL,
+                        make_select_lds<NT, HP_CPC, 8>(dyn_lds, sp.lds_bytes), &rr, cst, sp, split, rl,
+                        st.row_tickets + (int64_t)b * sp.F + f))
+    return;                                                // a shared row's segment, handed over
   finish_layer<NT>(st, sp, b, f, nf, split, rl, rr, dyn_lds, cls, cst.dst,
                    [&](RowResult& r) { if (TOPM) top_m_of_split_row<1, NT>(rowp, V, sp.M, r); });
 }

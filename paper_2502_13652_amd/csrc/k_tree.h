@@ -114,6 +114,11 @@ constexpr int SP_MAX_F = 64;
 constexpr int C2T_MAX_BUDGET_DEV = 1024;                  // n_out limit of the reranking
 constexpr int C2T_MAX_CANDIDATES_DEV = 2048;              // F*K limit of the per-sequence step
 
+// What a workgroup that shares a row hands over besides its counts and cell keys.
+struct __attribute__((aligned(32))) CoopAcc {
+  double s_tiny; int32_t n_tiny, n_masked; uint32_t mag_max, max_pattern;   // see OutsideAcc; max_pattern: packed maximum of the segment's bf16 patterns
+};
+
 struct ScoreParams {
   RowPartial* part; float* part_topv; int32_t* part_topi;    // [launched row][split] records and their top-K lists
   int nsplit, rows_per_seq, B, F, K, N, h, layer, D;
@@ -122,6 +127,13 @@ struct ScoreParams {
   int w_lds_off;                                             // byte offset of the classifier's copy in dynamic LDS, -1: none
   int compact;                                               // 1: workgroup w takes the w-th live row (see row_of_workgroup)
   float z_beta;
+  // Shared rows of the histogram path (coop > 1, then nsplit == 1): `coop` workgroups count one row's
+  // segments and hand their counts over through memory; the last to arrive runs the row's epilogue.
+  int coop;
+  int coop_map_stride;                                       // keys per row in coop_map (a multiple of 8)
+  uint32_t* coop_hist;                                       // [launched row][coop][HP_WORDS] counts of a segment
+  uint16_t* coop_map;                                        // [launched row][coop_map_stride] cell keys of the whole row
+  CoopAcc* coop_acc;                                         // [launched row][coop]
 };
 
 // What one workgroup of the logits pass leaves in LDS for its (row, split): the record and the

@@ -4,7 +4,8 @@ per phase boundary of the layer kernel, when the workgroups pass it (microsecond
 workgroup's start), the mean time between boundaries and the timeline of the workgroup that finishes last.
 
     python -m paper_2502_13652_amd.phase_times cfg4 2 --full     # a full layer (beta = 0) of cfg4
-    python -m paper_2502_13652_amd.phase_times cfg3 2            # 16 workgroups, each alone on a CU
+    python -m paper_2502_13652_amd.phase_times cfg3 2            # 16 rows, five workgroups each, all alone on their CUs
+    python -m paper_2502_13652_amd.phase_times cfg3 2 --unshared # 16 workgroups, one per row
 """
 import argparse
 import ctypes
@@ -39,6 +40,7 @@ def main():
     ap.add_argument("workload")
     ap.add_argument("layer", type=int)
     ap.add_argument("--full", action="store_true", help="beta = 0: every frontier stays full until the budget is used up")
+    ap.add_argument("--unshared", action="store_true", help="one workgroup per row also where rows would be shared")
     ap.add_argument("--no-build", action="store_true")
     a = ap.parse_args()
     import numpy as np
@@ -57,13 +59,16 @@ def main():
     layers = [W.logits_layer(cfg, l, device=gen).to(dev) for l in range(a.layer + 1)]
     ctx = binding.C2TContext(B, V, F, K, D, N, h, 0 if cfg["dtype"] == "f32" else 1, 0.0 if a.full else cfg["beta"], device=dev)
     ctx.set_classifier(*cls)
+    if a.unshared:
+        ctx.set_row_splits(1, 1)
+    per_row = ctx.row_workgroups()[0 if a.layer == 0 else 1]
     for _ in range(3):
         ctx.reset()
         for l in range(a.layer + 1):
             ctx.expand_layer(layers[l])
         torch.cuda.synchronize()
     rows = int(ctx.layer_rows().cpu().numpy()[a.layer])
-    nwg = min(8192, B * (F if a.layer > 0 else 1))
+    nwg = min(8192, B * (F if a.layer > 0 else 1) * per_row)
     buf = (ctypes.c_uint64 * (nwg * 16))()
     L.c2t_phase_times_read.argtypes = [ctypes.c_void_p, ctypes.c_int32]
     rc = L.c2t_phase_times_read(buf, nwg)
@@ -73,7 +78,9 @@ def main():
     t0 = t[:, 0].min()
     t[t < t0] = np.nan                                    # slots not passed in this launch hold older times
     us = (t - t0) / 100.0
-    print("%s layer %d%s: %d rows consumed, %d workgroups with a row" % (a.workload, a.layer, " (full)" if a.full else "", rows, len(us)))
+    print("%s layer %d%s: %d rows consumed, %d workgroups with a row (%d per row)" % (a.workload, a.layer, " (full)" if a.full else "", rows, len(us), per_row))
+    if per_row > 1:
+        print("(the workgroups that hand a segment's counts over end after 'histogram complete'; 'sums' includes the hand-over)")
     print("%-26s %8s %8s %8s %6s" % ("boundary", "mean us", "min", "max", "n"))
     for i, nm in enumerate(MARKS):
         c = us[:, i]

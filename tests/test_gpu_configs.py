@@ -227,6 +227,8 @@ def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():
         g = make_gpu(cfg, cls)
         if splits != (0, 0):
             g.set_row_splits(*splits)
+        # by default the 16 rows of a layer (and the root row) are shared by four workgroups each; a count that is set is taken literally
+        assert g.row_workgroups() == ((4, 4) if splits == (0, 0) else splits)
         g.reset()
         for l in range(cfg["D"]):
             g.expand_layer(layers[l])
@@ -234,6 +236,8 @@ def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():
         torch.cuda.synchronize()
     for k in outs[0]:
         np.testing.assert_array_equal(outs[0][k], outs[1][k], err_msg="rerun differs in " + k)   # determinism
+    for k in outs[0]:                                   # shared rows add the same counts up: nothing differs from unshared rows
+        np.testing.assert_array_equal(outs[0][k], outs[2][k], err_msg="sharing rows changes " + k)
     for o in outs[2:]:
         for k in ("tokens", "parent", "position", "n_nodes", "mask", "status"):
             np.testing.assert_array_equal(outs[0][k], o[k], err_msg="split changes " + k)
@@ -241,7 +245,7 @@ def test_split_rows_give_the_same_tree_and_reruns_are_bitwise_equal():
             np.testing.assert_allclose(outs[0][k], o[k], rtol=1e-5)
 
 
-@pytest.mark.parametrize("name,opts", [("cfg2", {}), ("cfg4", {}), ("cfg4", {"entropy_top_m": 1000}), ("cfg2", {"rerank": 1})])
+@pytest.mark.parametrize("name,opts", [("cfg2", {}), ("cfg3", {}), ("cfg4", {}), ("cfg4", {"entropy_top_m": 1000}), ("cfg2", {"rerank": 1})])
 def test_a_draft_phase_replayed_from_a_hip_graph(name, opts):
     """reset -> D x expand -> finalize captured once and replayed: every replay, with eager work of
     the same context and synchronisations in between, gives the eager result bit for bit (the

@@ -95,6 +95,32 @@ def test_workspace_and_state_errors(lib):
     assert lib.c2t_strerror(0) == b"ok" and b"workspace" in lib.c2t_strerror(-3) and b"memory" in lib.c2t_strerror(-6)
 
 
+def test_rows_shared_by_workgroups_launch_shape(lib):
+    """Host logic only (no device: 256 CUs assumed): which launches let several workgroups count one row."""
+    def per_row(c, splits=None):
+        need = ctypes.c_size_t()
+        assert lib.c2t_workspace_bytes(ctypes.byref(c), ctypes.byref(need)) == 0
+        ctx = ctypes.c_void_p()
+        assert lib.c2t_create(ctypes.byref(c), ctypes.c_void_p(0x10000), need.value, ctypes.byref(ctx)) == 0
+        if splits:
+            assert lib.c2t_set_row_splits(ctx, *splits) == 0
+        a, b = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        assert lib.c2t_get_row_workgroups(ctx, ctypes.byref(a), ctypes.byref(b)) == 0
+        assert lib.c2t_get_row_workgroups(ctx, None, None) == 0 and lib.c2t_get_row_workgroups(None, None, None) == -1
+        lib.c2t_destroy(ctx)
+        return a.value, b.value
+    one_seq = dict(batch=1, vocab=152064, max_frontier=16, top_k=16, max_depth=8, budget=96, hidden=32)
+    assert per_row(cfg(**one_seq)) == (5, 5)                      # ten groups of 32 KB: five workgroups with two each
+    assert per_row(cfg(**one_seq), (1, 0)) == (1, 5) and per_row(cfg(**one_seq), (0, 2)) == (5, 2)   # a count that is set is taken literally
+    assert per_row(cfg(**dict(one_seq, batch=64, vocab=128256))) == (4, 1)    # 64 root rows on 256 CUs; 1024 rows are not shared
+    assert per_row(cfg(**dict(one_seq, batch=128, vocab=128256))) == (2, 1)
+    assert per_row(cfg(**dict(one_seq, batch=129, vocab=128256))) == (1, 1)
+    assert per_row(cfg(**dict(one_seq, vocab=49152))) == (1, 1)   # under four groups: the hand-over costs more than it saves
+    assert per_row(cfg(**dict(one_seq, vocab=49160))) == (4, 4)   # 6145 chunks, four groups: the last workgroup gets the last chunk alone
+    assert per_row(cfg(**dict(one_seq, vocab=65544))) == (5, 5)   # 8193 chunks: five groups, one each
+    assert per_row(cfg(**dict(one_seq, vocab=32000, logits_dtype=0))) == (4, 4)   # fp32 rows are split, not shared
+
+
 def test_no_cpu_fallback_and_no_oracle_in_the_product():
     """Without a GPU the binding raises instead of computing anything on the host, and nothing
     under the package imports, links or names the oracle."""

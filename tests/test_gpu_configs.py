@@ -306,6 +306,11 @@ LIMIT_CASES = {
     "dealt_rows_b100": (100, 3001, "bf16", 5, 8, 8, 8, 0.3, 12),
     "dealt_rows_b200_f32": (200, 1003, "f32", 4, 4, 4, 4, 0.3, 6),
     "dealt_rows_b256": (256, 517, "bf16", 4, 4, 4, 4, 0.4, 5),
+    # few long rows: several workgroups count one row and hand their histograms over.  Five sequences with ragged
+    # frontiers and small budgets (sequences without a frontier among shared rows), five workgroups per row, the last
+    # with nothing but the row's partial chunk; a hundred one-row sequences, two workgroups per row
+    "shared_rows_b5": (5, 65541, "bf16", 4, 8, 8, 8, 0.3, 14),
+    "shared_rows_b100": (100, 49163, "bf16", 3, 1, 4, 4, 0.3, 3),
     # hidden widths that are not multiples of four: the classifier's arrays then start off 16 bytes
     "odd_hidden_7": (3, 1500, "bf16", 3, 4, 4, 7, 0.3, 10),
     "odd_hidden_1": (2, 900, "bf16", 3, 4, 4, 1, 0.3, 10),

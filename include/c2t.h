@@ -228,7 +228,8 @@ int c2t_stream_read_rows(const void* dev_ptr, int32_t rows, size_t row_bytes, si
  * layer kernel's launches so far, 16 uint64 each: the 100 MHz wall-clock time at which the workgroup's
  * first thread last passed each phase boundary (start, end of its own stream, histogram complete, sums,
  * K-th largest value, cells listed, cells re-read, top K ranked, row scored and handed over, sequence
- * ticket taken, sequence pruned; unused slots keep their previous value).  Synchronises the device.
+ * ticket taken, sequence pruned, four steps inside the sequence's pruning, split row merged; unused slots keep
+ * their previous value).  Synchronises the device.
  * The normal build returns C2T_ERR_UNSUPPORTED. */
 int c2t_phase_times_read(uint64_t* out, int32_t n_workgroups);
 

@@ -12,7 +12,7 @@ constexpr int WAVE = 64;
 // out.  In the normal build the marks expand to nothing.
 constexpr int PT_WORKGROUPS = 8192, PT_SLOTS = 16;
 enum PhaseMark { PT_START = 0, PT_STREAM_END, PT_HIST_COMPLETE, PT_SUMS, PT_TAU, PT_CELLS_LISTED, PT_CELLS_READ, PT_RANKED,
-                 PT_PUBLISHED, PT_TICKET, PT_PRUNED, PT_PRUNE_LOADED, PT_PRUNE_FIRST, PT_PRUNE_PRESELECTED, PT_PRUNE_RANKED };
+                 PT_PUBLISHED, PT_TICKET, PT_PRUNED, PT_PRUNE_LOADED, PT_PRUNE_FIRST, PT_PRUNE_PRESELECTED, PT_PRUNE_RANKED, PT_MERGED };
 #ifdef C2T_PHASE_TIMES
 __device__ unsigned long long c2t_phase_times[PT_WORKGROUPS * PT_SLOTS];
 #define C2T_PT(i) do { if (threadIdx.x == 0 && blockIdx.x < c2t::PT_WORKGROUPS) c2t::c2t_phase_times[blockIdx.x * c2t::PT_SLOTS + (i)] = wall_clock64(); } while (0)
@@ -31,6 +31,13 @@ struct __attribute__((aligned(16))) RowPartial {
   int32_t n_top;  // entries of the segment's top list that are valid (<= K)
   uint32_t flags; // bit 0: NaN or +inf seen; bit 1 (informational): a bf16 segment took the two-pass path
 };
+
+// the record of an empty segment
+__device__ __forceinline__ RowPartial empty_partial() {
+  RowPartial r;
+  r.ref = -INFINITY; r.a = 0.0; r.Z = 0.0; r.S = 0.0; r.n_top = 0; r.flags = 0u;
+  return r;
+}
 
 // Device-coherent accesses for data one workgroup writes and another reads inside the same kernel:
 // they go to the coherence point, so neither side needs cache-wide write-backs or invalidations.
@@ -147,10 +154,12 @@ __device__ __forceinline__ int wave_scan_incl(int v) {
 // K-th largest (k >= 1) of the keys held by one wave, NV keys per lane (invalid keys = 0,
 // the smallest key).  Radix select from the most significant bit with wave ballots; the
 // result is wave-uniform.  If fewer than k keys are valid the result is 0.
-template <int NV>
+// LOW_BIT > 0: the select stops above that bit and the result has its low bits clear: the largest
+// such key that at least k keys reach (a lower bound of the k-th largest, for a fraction of the steps).
+template <int NV, int LOW_BIT = 0>
 __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&key)[NV], int k) {
   uint32_t prefix = 0, care = 0;
-  for (int bit = 31; bit >= 0; --bit) {
+  for (int bit = 31; bit >= LOW_BIT; --bit) {
     const uint32_t want = prefix | (1u << bit);
     const uint32_t cmask = care | (1u << bit);
     int cnt = 0;

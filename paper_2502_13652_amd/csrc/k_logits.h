@@ -37,6 +37,9 @@
 namespace c2t {
 
 constexpr int SEL_CELL_CAP = 256;              // size of the candidate-cell list
+#ifndef C2T_TAU_LOW_BIT
+#define C2T_TAU_LOW_BIT 16
+#endif
 
 // LDS the selection may use once the cell list is built: the element list ((value, id), 8 bytes
 // an entry, overlaying histogram and cell map) and the number of cells a launch may keep:
@@ -272,12 +275,6 @@ __device__ __forceinline__ int rank_list(int K, const SelectLds& sel, const int3
   return min(n_el, K);
 }
 
-__device__ __forceinline__ RowPartial empty_partial() {
-  RowPartial r;
-  r.ref = -INFINITY; r.a = 0.0; r.Z = 0.0; r.S = 0.0; r.n_top = 0; r.flags = 0u;
-  return r;
-}
-
 // Sum of Z and S over the workgroup in a fixed order (wave butterflies, then waves ascending).
 // Only thread 0 needs the totals: it leaves them in out[0..1] (LDS), so no lane keeps the
 // per-wave partials alive in registers.
@@ -451,6 +448,7 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
   if (bad) sh_bad = 1;
   const float m = block_max<NT>(M, red_f);          // barriers inside also publish map, lane_keys, sh_bad
   const bool seg_bad = sh_bad != 0;
+  C2T_PT(PT_STREAM_END);                            // (the marks of the histogram path, at the corresponding steps)
 
   // pass 2: Z = sum e^(x-m), S = sum (x-m) e^(x-m)
   double Z = 0.0, S = 0.0;
@@ -473,6 +471,7 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
     }
   }
   block_sum2<NT>(Z, S, red_d, sum_d);
+  C2T_PT(PT_SUMS);
   if (top_m > 0) {
     __syncthreads();
     if (!seg_bad && m > -INFINITY) top_m_sums<DT, NT>(rowp, sg, top_m, m, red_d, sum_m);
@@ -480,15 +479,20 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
     __syncthreads();
   }
 
-  // tau = K-th largest of the lane maxima: a lower bound of the K-th largest logit
+  // tau = K-th largest of the lane maxima, to its upper 16 bits (half the select's steps, each a
+  // ballot per key; a few more elements pass): a lower bound of the K-th largest logit
   if (wid == 0) {
     uint32_t keys[NW];
 #pragma unroll
     for (int v = 0; v < NW; ++v) keys[v] = lane_keys[v * WAVE + lane];
-    const uint32_t t = wave_kth_largest<NW>(keys, K);
+    uint32_t t = wave_kth_largest<NW, C2T_TAU_LOW_BIT>(keys, K);
+    // -inf's key with its low bits cleared is no number's key; every key that reaches it is at least -inf's
+    const uint32_t key_neg_inf = 0x007FFFFFu;             // = sortable_key(-INFINITY)
+    if (t != 0u && t < key_neg_inf) t = key_neg_inf;
     if (lane == 0) sh_tau = t;
   }
   __syncthreads();
+  C2T_PT(PT_TAU);
   uint32_t tau_key = sh_tau;
   float tau = tau_key ? key_to_float(tau_key) : -INFINITY;
   bool ties = false;
@@ -523,9 +527,12 @@ __device__ __noinline__ void generic_segment(const uint4* __restrict__ rowp, int
   }
   if (tid == 0) sh_cnt = 0;
   __syncthreads();
+  C2T_PT(PT_CELLS_LISTED);
   collect_cells<DT, NT, CPC>(rowp, sg.c0, sg.c1, V, tau, ties, cell_list, n_cells, sel, &sh_cnt);
   if (ties) tie_scan<DT, NT>(rowp, sg, V, tau, K, sel, &sh_cnt, scan_tmp);
+  C2T_PT(PT_CELLS_READ);
   const int n_top = rank_list<NT>(K, sel, &sh_cnt, rr->topv, rr->topi);
+  C2T_PT(PT_RANKED);
   if (tid == 0) {
     RowPartial r;
     r.ref = (double)m; r.a = (double)m; r.Z = sum_d[0]; r.S = sum_d[1]; r.n_top = seg_bad ? 0 : n_top; r.flags = (seg_bad ? 1u : 0u) | info_flags;
@@ -625,6 +632,7 @@ __global__ __launch_bounds__(NT) void k_logits_generic(
   const uint4* rowp = (const uint4*)((const char*)logits + row * row_stride_elems * (DT == 1 ? 2 : 4));
   const Segment sg = make_segment<T::EPC>(V, split, cps);
   __shared__ RowResult rr;
+  C2T_PT(PT_START);
   if (threadIdx.x == 0) rr.parent_P = st.fr_P[row];        // off the tail's critical path
   if (sg.ncell == 0) { if (threadIdx.x == 0) { rr.part = empty_partial(); rr.ZM = 0.0; rr.SM = 0.0; } }
   else generic_segment<DT, NT, 1>(rowp, V, K, nsplit > 1 ? 0 : sp.M, sg, dyn_lds, make_select_lds<NT, 1, T::EPC>(dyn_lds, sp.lds_bytes), &rr, 0u);   // split rows: see top_m_of_split_row

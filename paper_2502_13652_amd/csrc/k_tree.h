@@ -154,33 +154,60 @@ __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_lau
   const RowPartial* rp = sp.part + row_launched * nsplit;
   const float* tv = sp.part_topv + row_launched * nsplit * K;
   const int32_t* ti = sp.part_topi + row_launched * nsplit * K;
+  const int per_row = nsplit * K;
+  const bool staged = (size_t)per_row * 8 <= lds_bytes;      // the lists fit the staging area in LDS
+  // Everything the merge reads is requested before anything is waited for: one memory round trip instead of
+  // four dependent ones (maximum, records, list lengths, entries).  A thread's first list entry (all of them
+  // when the row's lists hold at most one entry a thread): requested whether valid or not, masked below.
+  const bool in0 = staged && tid < per_row;
+  int n_top0 = 0, i0 = -1; float v0 = 0.f;
+  if (in0) { n_top0 = ld_dev(&rp[tid / K].n_top); v0 = ld_dev(tv + tid); i0 = ld_dev(ti + tid); }
   if (tid < WAVE) {                                          // wave 0: the sums, one split per lane and step
     const int lane = tid;
     float Rf = -INFINITY; uint32_t fl = 0;                   // ref holds a logit: exact as a float
-    for (int q = lane; q < nsplit; q += WAVE) { Rf = fmaxf(Rf, (float)ld_dev(&rp[q].ref)); fl |= ld_dev(&rp[q].flags); }
-    Rf = wave_max(Rf);
-    fl = wave_reduce_u32(fl, 0u, [](uint32_t x, uint32_t y) { return x | y; });
-    const double R = (double)Rf;
     double Z = 0.0, S = 0.0;
-    for (int q = lane; q < nsplit; q += WAVE) {
-      const RowPartial pq = ld_dev(rp + q);
+    if (nsplit <= WAVE) {
+      RowPartial pq = empty_partial();
+      if (lane < nsplit) pq = ld_dev(rp + lane);
+      Rf = wave_max(lane < nsplit ? (float)pq.ref : -INFINITY);
+      fl = wave_reduce_u32(pq.flags, 0u, [](uint32_t x, uint32_t y) { return x | y; });
+      const double R = (double)Rf;
       if (pq.Z > 0.0 && pq.ref > -INFINITY) {
         const double da = pq.a - R, dl = pq.ref - R;         // re-reference to the row maximum R; dl <= 0
         const double sc = da == 0.0 ? 1.0 : exp(da);
-        Z += pq.Z * sc; S += (pq.S + dl * pq.Z) * sc;
+        Z = pq.Z * sc; S = (pq.S + dl * pq.Z) * sc;
+      }
+    } else {
+      for (int q = lane; q < nsplit; q += WAVE) { Rf = fmaxf(Rf, (float)ld_dev(&rp[q].ref)); fl |= ld_dev(&rp[q].flags); }
+      Rf = wave_max(Rf);
+      fl = wave_reduce_u32(fl, 0u, [](uint32_t x, uint32_t y) { return x | y; });
+      const double R = (double)Rf;
+      for (int q = lane; q < nsplit; q += WAVE) {
+        const RowPartial pq = ld_dev(rp + q);
+        if (pq.Z > 0.0 && pq.ref > -INFINITY) {
+          const double da = pq.a - R, dl = pq.ref - R;
+          const double sc = da == 0.0 ? 1.0 : exp(da);
+          Z += pq.Z * sc; S += (pq.S + dl * pq.Z) * sc;
+        }
       }
     }
+    const double R = (double)Rf;
     Z = wave_sum(Z); S = wave_sum(S);
     if (lane == 0) { rr.part.ref = R; rr.part.a = R; rr.part.Z = Z; rr.part.S = S; rr.part.flags = fl; rr.part.n_top = 0; }
   }
   // An entry's merged rank = number of entries of the row's lists ahead of it.
-  const int per_row = nsplit * K;
   float* sv = (float*)lds; int32_t* si = (int32_t*)(lds + (size_t)per_row * 4);
   __shared__ int32_t n_valid;
   if (tid == 0) n_valid = 0;
   __syncthreads();
-  if ((size_t)per_row * 8 <= lds_bytes) {
-    for (int ent = tid; ent < per_row; ent += nt) {
+  if (staged) {
+    if (in0) {
+      const bool ok = tid % K < n_top0;
+      sv[tid] = ok ? v0 : 0.f;
+      si[tid] = ok ? i0 : -1;
+      if (ok) atomicAdd(&n_valid, 1);
+    }
+    for (int ent = tid + nt; ent < per_row; ent += nt) {
       const int q = ent / K, e = ent % K;
       const bool ok = e < ld_dev(&rp[q].n_top);
       sv[ent] = ok ? ld_dev(tv + ent) : 0.f;
@@ -508,6 +535,7 @@ __device__ __forceinline__ void finish_layer(const TreeState& s, const ScorePara
     if (!last_arrival(s.row_tickets + (int64_t)b * sp.F + f, sp.nsplit)) return;
     merge_row(sp, row_launched, rr, lds, (size_t)sp.lds_bytes);
     after_merge(rr);
+    C2T_PT(PT_MERGED);
   }
   score_row(s, sp, b, f, rr, cls, cls_lds);
   C2T_PT(PT_PUBLISHED);

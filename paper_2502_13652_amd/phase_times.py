@@ -19,7 +19,8 @@ sys.path.insert(0, _ROOT)
 
 MARKS = ["start", "own stream ends", "histogram complete", "sums", "K-th largest known", "cells listed", "cells re-read",
          "top K ranked", "row scored, handed over", "sequence ticket", "sequence pruned",
-         "  candidates loaded", "  first pruning done", "  preselected", "  ranked and appended"]
+         "  candidates loaded", "  first pruning done", "  preselected", "  ranked and appended",
+         "  (split rows) row merged"]
 
 
 def build():

@@ -151,6 +151,32 @@ __device__ __forceinline__ int wave_scan_incl(int v) {
   return (int)u;
 }
 
+// Partial rank of an entry with value v (its own index: self) in a list of n values in LDS: how many of the
+// entries first4, first4 + 1, .. first4 + 3, first4 + step4, ... come before it in the order (value desc, then
+// `ahead_at_tie(index)` among equal values).  Four values per LDS read, the reads independent of each other, where a
+// read per value has every step wait out the LDS latency (a merge of 40 list entries: 1.5 us).
+// vals 16-byte aligned, first4 and step4 multiples of 4; up to three floats past the n-th are read and ignored.
+template <typename AheadAtTie>
+__device__ __forceinline__ int count_ahead4(const float* vals, int n, int first4, int step4, float v, int self, AheadAtTie ahead_at_tie) {
+  int rank = 0;
+  for (int o = first4; o < n; o += step4) {
+    const float4 q = *(const float4*)(vals + o);
+    const float qa[4] = {q.x, q.y, q.z, q.w};
+    uint32_t eq = 0;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bool in = o + t < n;
+      rank += in && qa[t] > v; eq |= (in && qa[t] == v ? 1u : 0u) << t;
+    }
+    if (self >= o && self < o + 4) eq &= ~(1u << (self - o));   // not the entry itself
+    while (eq) {                                                // ties: rare
+      const int t = __ffs(eq) - 1; eq &= eq - 1;
+      rank += ahead_at_tie(o + t) ? 1 : 0;
+    }
+  }
+  return rank;
+}
+
 // K-th largest (k >= 1) of the keys held by one wave, NV keys per lane (invalid keys = 0,
 // the smallest key).  Radix select from the most significant bit with wave ballots; the
 // result is wave-uniform.  If fewer than k keys are valid the result is 0.

@@ -201,29 +201,27 @@ __device__ __forceinline__ void merge_row(const ScoreParams& sp, int64_t row_lau
   if (tid == 0) n_valid = 0;
   __syncthreads();
   if (staged) {
+    // an unused slot of a list: below every entry in the order (value desc, id asc), -inf entries included
+    constexpr int32_t NO_ID = 0x7fffffff;
     if (in0) {
       const bool ok = tid % K < n_top0;
-      sv[tid] = ok ? v0 : 0.f;
-      si[tid] = ok ? i0 : -1;
+      sv[tid] = ok ? v0 : -INFINITY;
+      si[tid] = ok ? i0 : NO_ID;
       if (ok) atomicAdd(&n_valid, 1);
     }
     for (int ent = tid + nt; ent < per_row; ent += nt) {
       const int q = ent / K, e = ent % K;
       const bool ok = e < ld_dev(&rp[q].n_top);
-      sv[ent] = ok ? ld_dev(tv + ent) : 0.f;
-      si[ent] = ok ? ld_dev(ti + ent) : -1;
+      sv[ent] = ok ? ld_dev(tv + ent) : -INFINITY;
+      si[ent] = ok ? ld_dev(ti + ent) : NO_ID;
       if (ok) atomicAdd(&n_valid, 1);
     }
     __syncthreads();
     for (int ent = tid; ent < per_row; ent += nt) {
       const int vi = si[ent];
-      if (vi < 0) continue;
+      if (vi == NO_ID) continue;
       const float v = sv[ent];
-      int ahead = 0;
-      for (int o = 0; o < per_row; ++o) {
-        const int oi = si[o];
-        ahead += oi >= 0 && ((sv[o] > v) || (sv[o] == v && oi < vi));
-      }
+      const int ahead = count_ahead4(sv, per_row, 0, 4, v, ent, [&](int o) { return si[o] < vi; });
       if (ahead < K) { rr.topv[ahead] = v; rr.topi[ahead] = vi; }
     }
   } else {

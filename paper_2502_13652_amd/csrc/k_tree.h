@@ -297,7 +297,7 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
 // of at most 64 survivors (root layers, chains, narrow trees) leaves a lane at most eight values,
 // which it reads one at a time instead (measured: 1-2 us per layer of a single sequence).
 constexpr int PRUNE_HIST_WORDS = 2048;        // 4096 bins, two 16-bit counters per word
-constexpr int PRUNE_PRESELECT_MIN = 128;      // shorter lists are ranked directly
+constexpr int PRUNE_PRESELECT_MIN = 64;       // shorter lists are ranked directly (128: cfg1 and cfg2, 70-100 survivors a layer, 2-3 % slower)
 constexpr int PRUNE_SHORT_LIST = 64;          // up to here the lanes of a survivor read the list one value at a time
 
 __host__ __device__ inline size_t score_lds_bytes(int h, int FK) {

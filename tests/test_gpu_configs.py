@@ -173,6 +173,23 @@ def test_first_pruning_is_strict_at_equality(dtype):
     assert (go["n_nodes"] > 0).all()
 
 
+@pytest.mark.parametrize("F,K,N", [(10, 10, 30), (32, 32, 100), (64, 32, 200)])
+def test_candidates_with_equal_confidence_are_ranked_by_token_and_slot(F, K, N):
+    # Equal classifier logits are the rule deep in a tree (P too small to move the fp32 sum: the K children of a row
+    # share H and d).  The extreme cases: every candidate of a layer with the same z (zero weights), and z a function
+    # of the row alone (one unit on H): the second pruning is then decided by token id and frontier slot alone.
+    cfg = dict(idx=96, B=3, V=5000, dtype="bf16", D=4, F=F, K=K, h=4, beta=0.5, N=N,
+               zipf_s=1.0, sigma=(1.0, 4.0), spike_frac=0.0, desc="equal confidences")
+    layers = _layers(cfg, "ties")
+    zero = (np.zeros((4, 3), np.float32), np.zeros(4, np.float32), np.zeros(4, np.float32), 1.0)
+    go, oo, audit = run_both(cfg, zero, layers, tag="all z equal F=%d K=%d" % (F, K))
+    assert (go["n_nodes"] == N).all() and len(np.unique(go["conf"][:, :N])) == 1
+    W1 = np.zeros((4, 3), np.float32); W1[0, 1] = 1.0
+    on_h = (W1, np.zeros(4, np.float32), np.array([1, 0, 0, 0], np.float32), 0.25)
+    go, oo, audit = run_both(cfg, on_h, layers, tag="z from H alone F=%d K=%d" % (F, K))
+    assert (go["n_nodes"] == N).all()
+
+
 def test_reranked_finalize_with_whole_families_tied():
     # a classifier that grows with the depth: most children score above their parent, so their path
     # minimum equals the parent's and the reranking is decided by its tie rules (depth, then scoring order)

@@ -288,17 +288,20 @@ __device__ __forceinline__ void score_row(const TreeState& s, const ScoreParams&
 // ---- sequence level: both prunings of Sec. 4.2 with the node budget, tree append, next frontier.
 // Run by one whole workgroup once every row of the sequence has been scored.
 //
-// Survivors of the first pruning are compacted into LDS lists (z, token, candidate index).  Only the
-// n_keep best of them matter: when the list is long, a 4096-bin histogram over the top 12 bits of
-// the order-preserving key of z finds the bin that holds the n_keep-th largest z, and the list is
-// cut down to the survivors from that bin upwards before the exact ranking.  The ranking gives each
-// survivor to T = 2^tshift lanes, which split the list between them and read 32 values per step
-// (the LDS is busy with the neighbouring workgroups' histograms: dependent reads are slow); a list
-// of at most 64 survivors (root layers, chains, narrow trees) leaves a lane at most eight values,
-// which it reads one at a time instead (measured: 1-2 us per layer of a single sequence).
+// Survivors of the first pruning are compacted into LDS lists (a 64-bit key of z and token, and the
+// candidate index).  Only the n_keep best of them matter: when the list is long, a 4096-bin histogram
+// over the top 12 bits of the order-preserving key of z finds the bin that holds the n_keep-th largest z,
+// and the list is cut down to the survivors from that bin upwards before the exact ranking.  The ranking
+// gives each survivor to T = 2^tshift lanes, which split the list between them, two keys per LDS read.
+#ifndef C2T_PRUNE_PRESELECT_MIN
+#define C2T_PRUNE_PRESELECT_MIN 64
+#endif
+#ifndef C2T_PRUNE_UNDECIDED_MAX
+#define C2T_PRUNE_UNDECIDED_MAX 64
+#endif
 constexpr int PRUNE_HIST_WORDS = 2048;        // 4096 bins, two 16-bit counters per word
-constexpr int PRUNE_PRESELECT_MIN = 64;       // shorter lists are ranked directly (128: cfg1 and cfg2, 70-100 survivors a layer, 2-3 % slower)
-constexpr int PRUNE_SHORT_LIST = 64;          // up to here the lanes of a survivor read the list one value at a time
+constexpr int PRUNE_PRESELECT_MIN = C2T_PRUNE_PRESELECT_MIN;   // shorter lists are ranked directly
+constexpr int PRUNE_UNDECIDED_MAX = C2T_PRUNE_UNDECIDED_MAX; // the select stops once at most so many survivors share the selected digits
 
 __host__ __device__ inline size_t score_lds_bytes(int h, int FK) {
   (void)h;
@@ -311,11 +314,14 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   const int F = sp.F, K = sp.K, N = sp.N, layer = sp.layer;
   const float z_beta = sp.z_beta;
   const int FK = F * K, FKp = (FK + 31) & ~31;
-  float* sz = (float*)lds;                                   // survivors: z, token, candidate index
-  int32_t* stok = (int32_t*)(sz + FKp);
-  int32_t* sidx = stok + FKp;
+  // survivors: one 64-bit key each, (order-preserving key of z) << 32 | ~token, so that a greater key comes first in
+  // the order (z desc, token asc); and the candidate index, which breaks the remaining ties.  Equal z is common, not
+  // rare: deep in a tree P is too small to move the classifier's fp32 sum, and the K children of a row, which
+  // share H and d, all get the same z.
+  uint64_t* skey = (uint64_t*)lds;
+  int32_t* sidx = (int32_t*)(skey + FKp);
   uint32_t* hist = (uint32_t*)(sidx + FKp);
-  __shared__ int32_t n_surv, n_red, flags_or, sel_bin;
+  __shared__ int32_t n_surv, n_red, flags_or, sel_bin, sel_above, sel_count;
   __shared__ int32_t scan_w[NW];
   __shared__ int32_t new_tok[SP_MAX_F], new_pslot[SP_MAX_F], new_node[SP_MAX_F];
   __shared__ float new_P[SP_MAX_F], new_s[SP_MAX_F];
@@ -353,8 +359,9 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     if (k < per && i < ncand) {
       if (my_tok[k] >= 0 && my_z[k] > z_beta) {
         const int u = atomicAdd(&n_surv, 1);
-        sz[u] = my_z[k]; stok[u] = my_tok[k]; sidx[u] = i;
-        const uint32_t bin = sortable_key(my_z[k]) >> 20;
+        const uint32_t zk = sortable_key(my_z[k]);
+        skey[u] = ((uint64_t)zk << 32) | (uint32_t)~my_tok[k]; sidx[u] = i;
+        const uint32_t bin = zk >> 20;
         atomicAdd(&hist[bin >> 1], (bin & 1u) ? 0x10000u : 1u);
       }
     }
@@ -367,49 +374,77 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
   int ns = n_surv;
   const int n_keep = max(0, min(min(F, N - nn), ns));
   if (n_keep > 0 && ns > PRUNE_PRESELECT_MIN) {
-    // bin of the n_keep-th largest z: thread t owns words 2047-4t .. 2047-4t-3 (bins descending)
-    constexpr int WPT = PRUNE_HIST_WORDS / NT;
-    uint32_t w[WPT]; int c = 0;
+    // Radix select on the 64-bit keys, twelve bits a level, from the top: the histogram of the level's digit over
+    // the survivors that are still undecided (those whose higher digits equal the digits selected so far; at the
+    // first level all of them, counted during the first pruning) gives the digit at which the running count from
+    // the top reaches what is still needed; survivors below it are dropped.  Typical layers are done after one
+    // level (a dozen survivors left); layers of equal z go on into the token bits instead of ranking hundreds of
+    // tied survivors against each other.
+    int need = n_keep, shift = 52;                           // (uniform) still to be taken from the undecided; the level's digit is key >> shift
+    uint64_t prefix = 0ull;                                  // the digits selected so far: the undecided have key >> (shift + 12) == prefix
+    for (;;) {
+      // thread t owns words 2047-4t .. 2047-4t-3 (bins descending)
+      constexpr int WPT = PRUNE_HIST_WORDS / NT;
+      uint32_t w[WPT]; int c = 0;
 #pragma unroll
-    for (int j = 0; j < WPT; ++j) { w[j] = hist[PRUNE_HIST_WORDS - 1 - (tid * WPT + j)]; c += (int)(w[j] & 0xffffu) + (int)(w[j] >> 16); }
-    const int incl = wave_scan_incl(c);
-    if (lane == WAVE - 1) scan_w[wid] = incl;
-    __syncthreads();
-    int above = incl - c;
+      for (int j = 0; j < WPT; ++j) { w[j] = hist[PRUNE_HIST_WORDS - 1 - (tid * WPT + j)]; c += (int)(w[j] & 0xffffu) + (int)(w[j] >> 16); }
+      const int incl = wave_scan_incl(c);
+      if (lane == WAVE - 1) scan_w[wid] = incl;
+      __syncthreads();
+      int above = incl - c;
 #pragma unroll
-    for (int v = 0; v < NW; ++v) if (v < wid) above += scan_w[v];
-    if (above < n_keep && above + c >= n_keep) {             // exactly one thread
-      int run = above;
+      for (int v = 0; v < NW; ++v) if (v < wid) above += scan_w[v];
+      if (above < need && above + c >= need) {               // exactly one thread
+        int run = above;
 #pragma unroll
-      for (int j = 0; j < WPT; ++j) {
-        const int word = PRUNE_HIST_WORDS - 1 - (tid * WPT + j);
-        const int hi = (int)(w[j] >> 16), lo = (int)(w[j] & 0xffffu);
-        if (run < n_keep && run + hi >= n_keep) sel_bin = 2 * word + 1;
-        run += hi;
-        if (run < n_keep && run + lo >= n_keep) sel_bin = 2 * word;
-        run += lo;
+        for (int j = 0; j < WPT; ++j) {
+          const int word = PRUNE_HIST_WORDS - 1 - (tid * WPT + j);
+          const int hi = (int)(w[j] >> 16), lo = (int)(w[j] & 0xffffu);
+          if (run < need && run + hi >= need) { sel_bin = 2 * word + 1; sel_above = run; sel_count = hi; }
+          run += hi;
+          if (run < need && run + lo >= need) { sel_bin = 2 * word; sel_above = run; sel_count = lo; }
+          run += lo;
+        }
       }
-    }
-    __syncthreads();
-    // cut the list down, in place: read, barrier, write
-    const int cut = sel_bin;
-    float rz[PER]; int32_t rt[PER], ri[PER];
+      if (tid == 0) n_red = 0;
+      __syncthreads();
+      // cut the list down, in place: read, barrier, write
+      const uint64_t cut = (prefix << 12) | (uint64_t)(uint32_t)sel_bin;
+      const int undecided = sel_count;
+      need -= sel_above;
+      uint64_t rk[PER]; int32_t ri[PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const int u = tid + k * NT;
-      rz[k] = -INFINITY; rt[k] = 0; ri[k] = -1;
-      if (u < ns) { rz[k] = sz[u]; rt[k] = stok[u]; ri[k] = sidx[u]; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      if (ri[k] >= 0 && (int)(sortable_key(rz[k]) >> 20) >= cut) {
-        const int u = atomicAdd(&n_red, 1);
-        sz[u] = rz[k]; stok[u] = rt[k]; sidx[u] = ri[k];
+      for (int k = 0; k < PER; ++k) {
+        const int u = tid + k * NT;
+        rk[k] = 0ull; ri[k] = -1;
+        if (u < ns) { rk[k] = skey[u]; ri[k] = sidx[u]; }
       }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        if (ri[k] >= 0 && (rk[k] >> shift) >= cut) {
+          const int u = atomicAdd(&n_red, 1);
+          skey[u] = rk[k]; sidx[u] = ri[k];
+        }
+      }
+      for (int i = tid; i < PRUNE_HIST_WORDS; i += NT) hist[i] = 0u;   // for the next level, if there is one
+      __syncthreads();
+      ns = n_red;
+      if (undecided <= PRUNE_UNDECIDED_MAX || shift < 12) break;      // (uniform) few enough to rank; or the last whole digit done
+      prefix = cut; shift -= 12;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int u = tid + k * NT;
+        if (u < ns) {
+          const uint64_t key = skey[u];
+          if ((key >> (shift + 12)) == prefix) {
+            const uint32_t digit = (uint32_t)(key >> shift) & 0xfffu;
+            atomicAdd(&hist[digit >> 1], (digit & 1u) ? 0x10000u : 1u);
+          }
+        }
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    ns = n_red;
   }
   C2T_PT(PT_PRUNE_PRESELECTED);
   if (n_keep > 0) {
@@ -420,8 +455,10 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
     for (int u0 = 0; u0 < ns; u0 += ustride) {               // uniform trip count: every lane meets in the DPP sums
       const int u = u0 + (tid >> tshift);
       const bool mine = u < ns;
-      const float z = mine ? sz[u] : 0.f;
-      const int tok = mine ? stok[u] : 0, i = mine ? sidx[u] : 0;
+      const uint64_t key = mine ? skey[u] : 0ull;
+      const int i = mine ? sidx[u] : 0;
+      const float z = key_to_float((uint32_t)(key >> 32));
+      const int tok = (int)~(uint32_t)key;
       // what an appended node needs, requested before the ranking so that the latency overlaps it
       float P = 0.f, H = 0.f, par_s = INFINITY; int par = -1;
       if (mine && sub == 0) {
@@ -429,36 +466,17 @@ __device__ __forceinline__ void prune_sequence(const TreeState& s, const ScorePa
         P = ld_dev(s.c_P + o); H = ld_dev(s.c_H + o); par = s.fr_node[(int64_t)b * F + i / K];
         if (s.h_tok) par_s = s.fr_s[(int64_t)b * F + i / K];
       }
+      // rank = survivors with a greater key, and those with the same key (the same token under two parents, with
+      // the same z) and a lower candidate index; the survivor's T lanes take two keys a step each
       int rank = 0;
-      if (mine && ns <= PRUNE_SHORT_LIST) {                  // short list: one value per lane and step, at most eight steps
-        for (int v = sub; v < ns; v += T) {
-          const float q = sz[v];
-          if (q > z) rank += 1;
-          else if (q == z && v != u) {                       // ties in z: rare
-            const int tj = stok[v], ij = sidx[v];
-            rank += (tj < tok) || (tj == tok && ij < i);
-          }
-        }
-      } else if (mine) {
-        for (int v = sub * 32; v < ns; v += T * 32) {        // entries past ns are masked
-          float qa[32];
-#pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            const float4 q = *(const float4*)(sz + v + 4 * t);
-            qa[4 * t] = q.x; qa[4 * t + 1] = q.y; qa[4 * t + 2] = q.z; qa[4 * t + 3] = q.w;
-          }
-          uint32_t eq = 0;
-#pragma unroll
-          for (int t = 0; t < 32; ++t) {
-            const bool in = v + t < ns;
-            rank += in && qa[t] > z; eq |= (in && qa[t] == z ? 1u : 0u) << t;
-          }
-          if (u >= v && u < v + 32) eq &= ~(1u << (u - v));  // not the survivor itself
-          while (eq) {                                         // ties in z: rare
-            const int t = __ffs(eq) - 1; eq &= eq - 1;
-            const int tj = stok[v + t], ij = sidx[v + t];
-            rank += (tj < tok) || (tj == tok && ij < i);
-          }
+      if (mine) {
+        for (int v = sub * 2; v < ns; v += T * 2) {
+          const uint4 q = *(const uint4*)(skey + v);
+          const uint64_t k0 = ((uint64_t)q.y << 32) | q.x, k1 = ((uint64_t)q.w << 32) | q.z;
+          const bool in1 = v + 1 < ns;
+          rank += (int)(k0 > key) + (int)(in1 && k1 > key);
+          if (k0 == key && v != u) rank += (int)(sidx[v] < i);
+          if (in1 && k1 == key && v + 1 != u) rank += (int)(sidx[v + 1] < i);
         }
       }
       if (tshift >= 1) rank += (int)dpp_u32<C2T_DPP_QUAD_XOR1, 0xf>(0u, (uint32_t)rank);

@@ -189,6 +189,19 @@ def test_candidates_with_equal_confidence_are_ranked_by_token_and_slot(F, K, N):
     go, oo, audit = run_both(cfg, on_h, layers, tag="z from H alone F=%d K=%d" % (F, K))
     assert (go["n_nodes"] == N).all()
 
+    # every frontier node of a sequence with the same logits row: the same K tokens under every parent, with the
+    # same z: the selection is decided by the frontier slot, the last tie-break
+    def same_rows(l):
+        x = layers(l).clone()
+        x[:, 1:, :] = x[:, :1, :]
+        return x
+    go, oo, audit = run_both(cfg, zero, same_rows, tag="equal rows, all z equal F=%d K=%d" % (F, K))
+    assert (go["n_nodes"] == N).all()
+    for b in range(cfg["B"]):                           # layer 1: the lowest token ids, each from every slot in turn
+        first = min(F, K)
+        t = go["tokens"][b, first:first + min(F, N - first)]
+        assert (np.diff(t) >= 0).all() and len(set(t.tolist())) == -(-len(t) // first)
+
 
 def test_reranked_finalize_with_whole_families_tied():
     # a classifier that grows with the depth: most children score above their parent, so their path

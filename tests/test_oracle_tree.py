@@ -397,6 +397,40 @@ def test_tree_invariants(bf16):
     assert found, "no classifier seed produced a non-trivial tree"
 
 
+# ---------------- equal confidences: the second pruning's tie order ----------------
+@pytest.mark.parametrize("equal_rows", [False, True])
+def test_equal_confidences_are_ranked_by_token_then_slot(equal_rows):
+    # Sec. 4.2.2 ranks by confidence only; with every confidence equal (zero weights) the order is this build's
+    # tie rule alone: token id ascending, then frontier slot ascending.  Expected trees from plain python sorts.
+    rng = np.random.default_rng(77)
+    V, F, K, D, N, h = 40, 4, 5, 3, 11, 2
+    logits = random_logits(rng, D, F, V, scale=2.0)
+    if equal_rows:
+        logits[:, :, 1:, :] = logits[:, :, :1, :]            # the same K tokens under every parent
+    t = RefTree(1, V, F, K, D, N, h, 0, 0.5)
+    t.set_classifier(np.zeros((h, 3), f32), np.zeros(h, f32), np.zeros(h, f32), 1.0)
+    out = run(t, logits)
+    tokens, parents, frontier = [], [], [-1]
+    for l in range(D):
+        cand = []
+        for slot, par in enumerate(frontier):
+            x = logits[l][0][slot]
+            top = sorted(range(V), key=lambda j: (-float(x[j]), j))[:K]
+            cand += [(tok, slot, par) for tok in top]
+        keep = sorted(cand, key=lambda c: (c[0], c[1]))[:min(F, N - len(tokens))]
+        frontier = []
+        for tok, slot, par in keep:
+            frontier.append(len(tokens)); tokens.append(tok); parents.append(par)
+        if not frontier:
+            break
+    n = out["n_nodes"][0]
+    assert n == len(tokens) == N
+    np.testing.assert_array_equal(out["tokens"][0, :n], tokens)
+    np.testing.assert_array_equal(out["parent"][0, :n], parents)
+    if equal_rows:                                           # layer 1: the lowest token id, from slots 0, 1, 2, 3
+        assert tokens[4] == tokens[5] == tokens[6] == tokens[7] and parents[4:8] == [0, 1, 2, 3]
+
+
 # ---------------- brute force on tiny inputs ----------------
 @pytest.mark.parametrize("case", range(12))
 def test_against_second_implementation_tiny(case):
